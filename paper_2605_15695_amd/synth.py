@@ -1,0 +1,263 @@
+"""Seeded synthetic SpMM inputs shaped like the paper's workload classes.
+
+The paper evaluates on SNAP / DIMACS10 / OGB graphs (Section 6.1), which are not
+available offline.  These generators stand in for them: Poisson-degree uniform
+graphs, road-like geometric grids, R-MAT power-law graphs and stochastic block
+models, i.e. the locality / degree-distribution classes the paper's introduction
+and Section 6.1 describe.
+
+This module holds no SpMM or PCSR arithmetic.  It only draws graphs, edge values
+and dense operands from a seeded PCG64 stream, so the CPU oracle and the HIP path
+can be fed identical inputs.  Everything returned is a numpy array:
+``rowptr`` int32[n+1], ``colidx`` int32[nnz] (sorted, duplicate free per row),
+``vals`` float32[nnz].
+"""
+from __future__ import annotations
+
+import dataclasses
+
+import numpy as np
+
+BASE_SEED = 0xC0FFEE
+
+
+@dataclasses.dataclass
+class Graph:
+    name: str
+    n_rows: int
+    n_cols: int
+    rowptr: np.ndarray
+    colidx: np.ndarray
+    vals: np.ndarray
+
+    @property
+    def nnz(self) -> int:
+        return int(self.colidx.shape[0])
+
+    def degrees(self) -> np.ndarray:
+        return np.diff(self.rowptr.astype(np.int64))
+
+
+def _rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def csr_from_edges(n_rows: int, n_cols: int, src: np.ndarray, dst: np.ndarray):
+    """Sort (src, dst) pairs row-major, drop duplicates, return (rowptr, colidx)."""
+    key = src.astype(np.int64) * np.int64(n_cols) + dst.astype(np.int64)
+    key = np.unique(key)
+    rows = key // np.int64(n_cols)
+    colidx = (key - rows * np.int64(n_cols)).astype(np.int32)
+    counts = np.bincount(rows, minlength=n_rows)
+    rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+    np.cumsum(counts, out=rowptr[1:])
+    assert rowptr[-1] < 2**31
+    return rowptr.astype(np.int32), colidx
+
+
+def values_inv_row_degree(rowptr: np.ndarray) -> np.ndarray:
+    """a_ij = 1/deg(i): mean aggregation."""
+    deg = np.diff(rowptr.astype(np.int64))
+    return np.repeat(1.0 / np.maximum(deg, 1), deg).astype(np.float32)
+
+
+def values_gcn(rowptr: np.ndarray, colidx: np.ndarray, n_cols: int) -> np.ndarray:
+    """a_ij = 1/sqrt(max(1,outdeg_i) * max(1,indeg_j)); for a symmetric pattern this
+    is the usual 1/sqrt(deg_i deg_j) GCN normalisation."""
+    outdeg = np.diff(rowptr.astype(np.int64))
+    indeg = np.bincount(colidx, minlength=n_cols)
+    ri = np.repeat(np.maximum(outdeg, 1).astype(np.float64), outdeg)
+    cj = np.maximum(indeg, 1).astype(np.float64)[colidx]
+    return (1.0 / np.sqrt(ri * cj)).astype(np.float32)
+
+
+def dense_operand(n: int, K: int, dist: str, seed: int) -> np.ndarray:
+    """B (n x K, row-major fp32): 'uniform' = U(-1,1), 'normal' = N(0,1)."""
+    rng = _rng(seed ^ 0xB0B)
+    if dist == "uniform":
+        B = rng.random((n, K), dtype=np.float32)
+        B *= 2.0
+        B -= 1.0
+        return B
+    if dist == "normal":
+        return rng.standard_normal((n, K), dtype=np.float32)
+    raise ValueError(dist)
+
+
+# --------------------------------------------------------------------------- C1
+def poisson_uniform(n: int = 4096, mean_deg: float = 8.0, seed: int = BASE_SEED + 1) -> Graph:
+    """Each row draws Poisson(mean_deg) distinct uniformly random column ids; 1/deg values."""
+    rng = _rng(seed)
+    deg = np.minimum(rng.poisson(mean_deg, n), n)
+    src = np.repeat(np.arange(n, dtype=np.int64), deg)
+    dst = np.empty(src.shape[0], dtype=np.int64)
+    pos = 0
+    for i in range(n):
+        d = int(deg[i])
+        if d:
+            dst[pos:pos + d] = rng.choice(n, size=d, replace=False)
+            pos += d
+    rowptr, colidx = csr_from_edges(n, n, src, dst)
+    return Graph("poisson_uniform", n, n, rowptr, colidx, values_inv_row_degree(rowptr))
+
+
+# --------------------------------------------------------------------------- C2
+def road_grid(width: int = 2000, height: int = 1000, mean_draw: float = 2.1,
+              seed: int = BASE_SEED + 2) -> Graph:
+    """Road-like geometric graph: one node per cell of a width x height grid, ids in
+    row-major grid order, each node displaced by a uniform jitter inside its cell.
+    A node draws m ~ Poisson(mean_draw) and links to its m geometrically nearest
+    nodes among the 8 surrounding cells; links are made undirected and deduplicated,
+    so (mutual picks collapsing) the mean degree is about 3 for the default mean_draw and
+    neighbours are near in id order.
+    GCN-normalised values."""
+    rng = _rng(seed)
+    n = width * height
+    ids = np.arange(n, dtype=np.int64)
+    x = (ids % width).astype(np.int32)
+    y = (ids // width).astype(np.int32)
+    jx = rng.uniform(-0.4, 0.4, n).astype(np.float32)
+    jy = rng.uniform(-0.4, 0.4, n).astype(np.float32)
+    m = np.minimum(rng.poisson(mean_draw, n), 8).astype(np.int8)
+    offs = [(-1, -1), (0, -1), (1, -1), (-1, 0), (1, 0), (-1, 1), (0, 1), (1, 1)]
+    dist = np.empty((n, 8), dtype=np.float32)
+    for k, (dx, dy) in enumerate(offs):
+        nx, ny = x + dx, y + dy
+        ok = (nx >= 0) & (nx < width) & (ny >= 0) & (ny < height)
+        nid = np.where(ok, ny.astype(np.int64) * width + nx, 0)
+        ddx = (dx + jx[nid]) - jx
+        ddy = (dy + jy[nid]) - jy
+        d2 = ddx * ddx + ddy * ddy
+        dist[:, k] = np.where(ok, d2, np.float32(np.inf))
+    order = np.argsort(dist, axis=1, kind="stable")
+    srcs, dsts = [], []
+    for r in range(8):
+        k = order[:, r]
+        take = (m > r) & np.isfinite(dist[ids, k])
+        u = ids[take]
+        kk = k[take]
+        dxs = np.array([o[0] for o in offs], dtype=np.int64)[kk]
+        dys = np.array([o[1] for o in offs], dtype=np.int64)[kk]
+        v = (y[take].astype(np.int64) + dys) * width + (x[take].astype(np.int64) + dxs)
+        srcs.append(u)
+        dsts.append(v)
+    u = np.concatenate(srcs)
+    v = np.concatenate(dsts)
+    src = np.concatenate([u, v])
+    dst = np.concatenate([v, u])
+    rowptr, colidx = csr_from_edges(n, n, src, dst)
+    return Graph("road_grid", n, n, rowptr, colidx, values_gcn(rowptr, colidx, n))
+
+
+# ---------------------------------------------------------------------- C3 / C5
+def _rmat_edges(scale: int, n_edges: int, a: float, b: float, c: float,
+                rng: np.random.Generator, chunk: int = 1 << 24):
+    src = np.empty(n_edges, dtype=np.int64)
+    dst = np.empty(n_edges, dtype=np.int64)
+    ab, abc = np.float32(a + b), np.float32(a + b + c)
+    a32 = np.float32(a)
+    for lo in range(0, n_edges, chunk):
+        hi = min(n_edges, lo + chunk)
+        s = np.zeros(hi - lo, dtype=np.int64)
+        d = np.zeros(hi - lo, dtype=np.int64)
+        for _ in range(scale):
+            r = rng.random(hi - lo, dtype=np.float32)
+            sbit = r >= ab
+            dbit = ((r >= a32) & (r < ab)) | (r >= abc)
+            s = (s << 1) | sbit
+            d = (d << 1) | dbit
+        src[lo:hi] = s
+        dst[lo:hi] = d
+    return src, dst
+
+
+def rmat(scale: int = 20, edge_factor: int = 16, a: float = 0.57, b: float = 0.19,
+         c: float = 0.19, symmetric: bool = False, permute: bool = True,
+         min_dmax: int = 0, seed: int = BASE_SEED + 3) -> Graph:
+    """R-MAT graph with 2**scale nodes and edge_factor * 2**scale edge draws,
+    self loops kept, duplicates removed.  ``permute`` relabels node ids with a random
+    permutation (poor locality); ``symmetric`` adds the reverse of every edge.
+    If ``min_dmax`` > 0 and the largest row is shorter, the busiest node receives
+    extra undirected edges to targets drawn with probability proportional to current
+    degree (Chung-Lu style) until its row is long enough.  GCN-normalised values."""
+    rng = _rng(seed)
+    n = 1 << scale
+    src, dst = _rmat_edges(scale, edge_factor * n, a, b, c, rng)
+    if permute:
+        perm = rng.permutation(n).astype(np.int64)
+        src, dst = perm[src], perm[dst]
+    if symmetric:
+        src, dst = np.concatenate([src, dst]), np.concatenate([dst, src])
+    rowptr, colidx = csr_from_edges(n, n, src, dst)
+    del src, dst
+    if min_dmax:
+        deg = np.diff(rowptr.astype(np.int64))
+        hub = int(np.argmax(deg))
+        if deg[hub] < min_dmax:
+            p = deg.astype(np.float64)
+            p /= p.sum()
+            extra = rng.choice(n, size=int(2.5 * (min_dmax - deg[hub])) + 1024, p=p)
+            rows = np.repeat(np.arange(n, dtype=np.int64), deg)
+            hubs = np.full(extra.shape[0], hub, dtype=np.int64)
+            s2 = np.concatenate([rows, hubs, extra])
+            d2 = np.concatenate([colidx.astype(np.int64), extra, hubs])
+            rowptr, colidx = csr_from_edges(n, n, s2, d2)
+    name = f"rmat{scale}" + ("_sym" if symmetric else "") + ("_perm" if permute else "")
+    return Graph(name, n, n, rowptr, colidx, values_gcn(rowptr, colidx, n))
+
+
+# --------------------------------------------------------------------------- C4
+def sbm(n: int = 250_000, n_blocks: int = 500, mean_deg: float = 50.0, p_intra: float = 0.9,
+        shuffled: bool = False, seed: int = BASE_SEED + 4) -> Graph:
+    """Stochastic block model: equal blocks of consecutive ids; each row draws
+    Poisson(mean_deg) edges, each inside its own block with probability p_intra
+    (uniform over the block) and uniform over all nodes otherwise; duplicates removed.
+    ``shuffled`` applies a random relabelling to the same graph.  1/deg values."""
+    rng = _rng(seed)
+    bs = n // n_blocks
+    assert bs * n_blocks == n
+    deg = rng.poisson(mean_deg, n)
+    src = np.repeat(np.arange(n, dtype=np.int64), deg)
+    total = src.shape[0]
+    intra = rng.random(total, dtype=np.float32) < np.float32(p_intra)
+    dst = np.where(intra, (src // bs) * bs + rng.integers(0, bs, total),
+                   rng.integers(0, n, total))
+    if shuffled:
+        perm = _rng(seed ^ 0x5EED).permutation(n).astype(np.int64)
+        src, dst = perm[src], perm[dst]
+    rowptr, colidx = csr_from_edges(n, n, src, dst)
+    return Graph("sbm_shuffled" if shuffled else "sbm_clustered", n, n, rowptr, colidx,
+                 values_inv_row_degree(rowptr))
+
+
+# ------------------------------------------------------------------- workloads
+# name -> (graph factory, B distribution, default K list).  "full" sizes follow the
+# benchmark configurations; "small" sizes are what the CPU oracle finishes in seconds.
+def workload(name: str, size: str = "full") -> Graph:
+    full = size == "full"
+    if name == "poisson":
+        return poisson_uniform(4096 if full else 1024)
+    if name == "road":
+        return road_grid(2000, 1000) if full else road_grid(211, 97)
+    if name == "rmat20":
+        return rmat(20 if full else 13, 16, permute=True, symmetric=False)
+    if name == "sbm":
+        return sbm(250_000, 500) if full else sbm(12_000, 24)
+    if name == "sbm_shuffled":
+        return sbm(250_000, 500, shuffled=True) if full else sbm(12_000, 24, shuffled=True)
+    if name == "rmat22":
+        if full:
+            return rmat(22, 16, permute=False, symmetric=True, min_dmax=100_001,
+                        seed=BASE_SEED + 5)
+        return rmat(14, 16, permute=False, symmetric=True, seed=BASE_SEED + 5)
+    raise ValueError(name)
+
+
+WORKLOADS = {
+    "poisson": dict(B="uniform", K=[32]),
+    "road": dict(B="normal", K=[128]),
+    "rmat20": dict(B="normal", K=[64]),
+    "sbm": dict(B="uniform", K=[256]),
+    "sbm_shuffled": dict(B="uniform", K=[256]),
+    "rmat22": dict(B="normal", K=[16, 32, 64, 128, 256, 512]),
+}
