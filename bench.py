@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the PCSR SpMM hot path on one MI355X.
+
+A step is one C = A*B over the whole synthetic workload (PCSR traversal, B gather + FMA,
+write-back), with the PCSR arrays, B and C already resident in HBM.  PCSR generation and
+feature extraction are one-off per graph (the paper amortises them over training
+iterations) and are reported in separate fields, outside the timed region.
+
+Prints ONE JSON line: metric/value (GFLOP/s = 2*nnz*K / t), the HBM roofline of the SpMM
+kernel measured live with device events, and the CPU oracle timed on this machine's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(g, K: int) -> int:
+    """Minimum HBM traffic of one SpMM: colidx + val once, rowptr once, every referenced
+    B row once, C once."""
+    n_refcols = int(np.unique(g.colidx).shape[0])
+    return g.nnz * 8 + (g.n_rows + 1) * 4 + n_refcols * K * 4 + g.n_rows * K * 4
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="road", help="road | rmat20 | sbm | sbm_shuffled | poisson | rmat22")
+    ap.add_argument("--K", type=int, default=0, help="0 = the workload's benchmark width")
+    ap.add_argument("--size", default="full", choices=["full", "small"])
+    ap.add_argument("--V", type=int, default=-1, help="-1 = library selector")
+    ap.add_argument("--S", type=int, default=-1)
+    ap.add_argument("--SG", type=int, default=0)
+    ap.add_argument("--lanes-per-row", type=int, default=0)
+    ap.add_argument("--vec", type=int, default=0)
+    ap.add_argument("--rep", type=int, default=0)
+    ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--no-xcd-remap", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no sharded path exists)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2605_15695_amd as pc
+    from paper_2605_15695_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    t0 = time.time()
+    g = synth.workload(args.workload, args.size)
+    spec = synth.WORKLOADS[args.workload]
+    K = args.K or spec["K"][0]
+    B = synth.dense_operand(g.n_cols, K, spec["B"], 2)
+    gen_s = time.time() - t0
+
+    t0 = time.time()
+    feats = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
+    sel = pc.pcsr_select(feats, K)
+    feat_ms = (time.time() - t0) * 1e3
+    V = sel.V if args.V < 0 else args.V
+    S = sel.S if args.S < 0 else args.S
+    params = pc.make_params(V=V, S=S, SG=args.SG, lanes_per_row=args.lanes_per_row, vec=args.vec,
+                            rep=args.rep, waves_per_wg=args.waves,
+                            flags=pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
+    t0 = time.time()
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, params)
+    build_ms = (time.time() - t0) * 1e3
+    launch = pc.pcsr_query_launch(h, K)
+
+    Bd = torch.from_numpy(B).cuda()
+    Cd = torch.empty((g.n_rows, K), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        pc.pcsr_spmm(h, Bd, Cd, K, stream)
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` SpMMs, each bracketed by events on the launch stream
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    for a, b in evs:
+        a.record(stream)
+        pc.pcsr_spmm(h, Bd, Cd, K, stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    per_launch_ms = [a.elapsed_time(b) for a, b in evs]
+    ms_per_step = wall * 1e3 / args.steps
+    kern_ms = statistics.fmean(per_launch_ms)
+
+    flops = 2.0 * g.nnz * K
+    bytes_min = algorithmic_bytes(g, K)
+    achieved = bytes_min / (kern_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "SpMM GFLOP/s (2*nnz*K)",
+        "value": flops / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}-{args.size}", "graph": g.name, "n": g.n_rows,
+                   "nnz": g.nnz, "K": K, "V": V, "S": S, **launch},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_ms_mean": kern_ms, "kernel_ms_median": statistics.median(per_launch_ms),
+                     "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": bytes_min},
+        "setup": {"generate_s": gen_s, "features_select_ms": feat_ms, "pcsr_build_ms": build_ms},
+    }
+
+    if not args.no_check or not args.no_cpu_baseline:
+        import oracle
+
+        # the oracle as it stands, on this machine's host cores
+        if g.nnz * K <= 2.5e9:
+            rows, sample = None, "full workload, best of 3"
+            reps = 3
+        else:
+            n_s = max(1, int(g.n_rows * 2.5e9 / (g.nnz * K)))
+            rows = np.sort(np.random.default_rng(0).choice(g.n_rows, n_s, replace=False)).astype(np.int64)
+            sample, reps = f"{n_s} random rows of {g.n_rows}, 1 run", 1
+        best = float("inf")
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            if rows is None:
+                ref, bound = oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+            else:
+                ref, bound = oracle.spmm_rows(g.rowptr, g.colidx, g.vals, B, rows)
+            best = min(best, time.perf_counter() - t0)
+        if rows is None:
+            cpu_flops = flops
+            got = Cd.cpu().numpy()
+        else:
+            cpu_flops = 2.0 * float(np.diff(g.rowptr.astype(np.int64))[rows].sum()) * K
+            got = Cd[torch.from_numpy(rows).cuda()].cpu().numpy()
+        ok, worst = oracle.within_tolerance(got, ref, bound)
+        out["cpu_baseline"] = {"value": cpu_flops / best / 1e9, "unit": "GFLOP/s",
+                               "cores": oracle.max_threads(), "kind": "oracle", "sample": sample}
+        out["parity"] = {"ok": bool(ok), "worst_err_over_limit": worst}
+        if not ok:
+            print(json.dumps(out))
+            print("bench.py: GPU result is outside tolerance", file=sys.stderr)
+            return 1
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

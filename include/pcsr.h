@@ -1,0 +1,170 @@
+/*
+ * pcsr.h - C ABI of the PCSR SpMM library for AMD MI355X (gfx950).
+ *
+ * Computes C = A * B where A (n_rows x n_cols, sparse) is held in the paper's
+ * Parameterized CSR form and B (n_cols x K) and C (n_rows x K) are dense, row-major,
+ * fp32 (problem statement: Section 2, "Background"; format: Section 4.2; kernel:
+ * Algorithm 2 in Section 4.3).
+ *
+ * Conventions for every entry point
+ *   - return value: PCSR_OK (0) or a negative PCSR_E_* code; nothing is thrown across
+ *     the ABI; output arguments are left untouched on failure.
+ *   - "host" / "device" in an argument's description says where the memory must live.
+ *   - the library never synchronises the caller's stream unless stated.
+ */
+#ifndef PCSR_H
+#define PCSR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    PCSR_OK = 0,
+    PCSR_E_INVALID_ARG = -1, /* null pointer, negative size, misaligned B/C, bad handle      */
+    PCSR_E_BAD_CSR = -2,     /* rowptr not monotone / not starting at 0 / not ending at nnz,
+                                column out of range, columns of a row not strictly ascending  */
+    PCSR_E_UNSUPPORTED = -3, /* V not in {1,2}, K <= 0, vec does not divide K, bad kernel
+                                parameter, SpMM on a host-only handle                        */
+    PCSR_E_TOO_LARGE = -4,   /* nnz, n_rows or the item count does not fit int32             */
+    PCSR_E_OOM = -5,         /* host or device allocation failed                             */
+    PCSR_E_HIP = -6          /* a HIP runtime call failed (see pcsr_last_hip_error)          */
+};
+
+enum {
+    PCSR_FLAG_DEVICE_CSR = 1,  /* rowptr/colidx/vals passed to pcsr_build are device pointers */
+    PCSR_FLAG_NO_VALIDATE = 2, /* trust the CSR (skips the O(nnz) check)                      */
+    PCSR_FLAG_NO_XCD_REMAP = 4,/* keep the hardware's round-robin workgroup -> XCD order      */
+    PCSR_FLAG_HOST_ONLY = 8    /* build the arrays on the host only (no GPU needed); the
+                                  handle serves pcsr_export but not pcsr_spmm                 */
+};
+
+/*
+ * The configuration tuple of Section 3.4 / 4.1, re-expressed for 64-lane wavefronts.
+ *   Format parameters (change the PCSR arrays):
+ *     V      vector size: rows per panel, 1 or 2 (Section 3.1 limits V to {1,2}).
+ *     S      0/1 workload balancing (Section 3.2): cap every work item at SG vectors.
+ *     SG     split granularity; 0 = Eq. (3) with `omega`, > 0 = use as given.
+ *     omega  lane count used by Eq. (3); 0 = 64 (wavefront).  32 gives the paper's SG.
+ *   Kernel parameters (launch shape only; the paper's F and W):
+ *     lanes_per_row  lanes cooperating on one work item: 4, 8, 16, 32 or 64; 0 = auto.
+ *     vec            fp32 values per lane per B load: 1, 2 or 4; must divide K; 0 = auto.
+ *     rep            column tiles per lane (the coarsening factor F): 1, 2 or 4; 0 = auto.
+ *                    One work item covers lanes_per_row*vec*rep columns of C per grid.y
+ *                    slice; wider K is covered by more grid.y slices.
+ *     waves_per_wg   wavefronts per workgroup (the paper's W): 1, 2, 4 or 8; 0 = auto.
+ *   flags   PCSR_FLAG_* bits.
+ */
+typedef struct {
+    int32_t V;
+    int32_t S;
+    int32_t SG;
+    int32_t omega;
+    int32_t lanes_per_row;
+    int32_t vec;
+    int32_t rep;
+    int32_t waves_per_wg;
+    int32_t flags;
+    int32_t reserved[3]; /* must be 0 */
+} pcsr_params_t;
+
+typedef struct pcsr_handle_s *pcsr_handle_t;
+
+/*
+ * PCSR generation (Section 4.2, "PCSR Generation"): vectorised blocking of the CSR
+ * matrix into V x 1 nonzero vectors, then, if S, the workload split that rewrites
+ * rowPtr and emits TRow.
+ *   n_rows, n_cols, nnz : shape of A and its stored nonzeros (nnz < 2^31).
+ *   rowptr  int32[n_rows+1], colidx int32[nnz], vals fp32[nnz]: host memory, or device
+ *           memory when PCSR_FLAG_DEVICE_CSR is set.  Columns of each row must be
+ *           strictly ascending (sorted, no duplicates); explicit zeros are kept.
+ *   p       parameters; NULL = all defaults (V=1, S=0).
+ *   out     receives the handle.  The handle owns device copies of the PCSR arrays on
+ *           the device that is current at the call; the caller keeps ownership of the
+ *           CSR arrays and may free them on return.
+ * Errors: INVALID_ARG, BAD_CSR, UNSUPPORTED, TOO_LARGE, OOM, HIP.  Synchronous.
+ */
+int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+               const int32_t *colidx, const float *vals, const pcsr_params_t *p,
+               pcsr_handle_t *out);
+
+/*
+ * SpMM computing engine (Algorithm 2): C = A * B, overwriting C whatever it held.
+ *   B  device, fp32[n_cols x K] row-major, leading dimension K, aligned to 4*vec bytes.
+ *   C  device, fp32[n_rows x K] row-major, leading dimension K, same alignment; must
+ *      not overlap B.
+ *   K  > 0.  One handle serves any K.
+ *   stream  a hipStream_t (NULL = the null stream).  The work is enqueued there; the
+ *      call does not wait for it and allocates nothing.
+ * With S = 0 the result is bit-reproducible run to run.  With S = 1 rows that were
+ * split are accumulated with fp32 atomics, so their summation order may vary.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ */
+int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream);
+
+/* Releases the handle and its device arrays.  NULL is a no-op.  The caller must make
+ * sure no pcsr_spmm using the handle is still running. */
+int pcsr_free(pcsr_handle_t h);
+
+/*
+ * Changes the kernel-only parameters (lanes_per_row, vec, rep, waves_per_wg, and the
+ * PCSR_FLAG_NO_XCD_REMAP bit of flags) of an existing handle; 0 = auto.  The PCSR
+ * arrays are untouched, so one build can be timed under many launch shapes (the
+ * exhaustive sweep that stands in for the training data of Section 5.2).
+ * Errors: INVALID_ARG, UNSUPPORTED.
+ */
+int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, int32_t rep,
+                           int32_t waves_per_wg, int32_t flags);
+
+/*
+ * Reports the launch shape pcsr_spmm would use for width K with the handle's current
+ * kernel parameters (after "auto" resolution): out[0..5] = lanes_per_row, vec, rep,
+ * waves_per_wg, grid.x, grid.y.  Host memory.  Errors: INVALID_ARG, UNSUPPORTED.
+ */
+int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[6]);
+
+/*
+ * Copies the PCSR arrays (Section 4.2, "Data Representation") out of the handle for
+ * inspection.  sizes (host, int64[6]) receives P (panels), M (work items), nnz_V
+ * (vectors), V, SG, has_TRow.  Each of rowptr int32[M+1], colidx int32[nnz_V],
+ * val fp32[nnz_V*V], trow int32[M] (host) is filled when non-NULL; pass NULLs first
+ * to learn the sizes.  Synchronous (device -> host copies).  Errors: INVALID_ARG, HIP.
+ */
+int pcsr_export(pcsr_handle_t h, int64_t sizes[6], int32_t *rowptr, int32_t *colidx, float *val,
+                int32_t *trow);
+
+/*
+ * Sparse-matrix features of Table 3, in this order (host, fp64[PCSR_N_FEATURES]):
+ *   n, n_hat, nnz, delta, d, d_hat, d_max, CV, CV_hat, SR_1, SR_2, rho, b, b_max,
+ *   PR_1, PR_2      (SR: Eq. (4) under S with Eq. (3)'s SG; PR: Eq. (2)).
+ * rowptr/colidx: host.  omega as in pcsr_params_t (0 = 64).
+ * Errors: INVALID_ARG (n_out < PCSR_N_FEATURES, nulls), BAD_CSR.
+ */
+#define PCSR_N_FEATURES 16
+int pcsr_features(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                  const int32_t *colidx, int32_t omega, double *out, int32_t n_out);
+
+/*
+ * Configuration prediction (the role of the SpMM-decider, Section 5.2): maps the
+ * feature vector and K to a full parameter tuple with a rule distilled from recorded
+ * exhaustive sweeps on MI355X.  features: host fp64[PCSR_N_FEATURES]; out: host.
+ * Errors: INVALID_ARG, UNSUPPORTED (K <= 0).
+ */
+int pcsr_select(const double *features, int32_t K, pcsr_params_t *out);
+
+/* MAC-job gap of Eq. (1) for width dim, coarsening F and lane count omega (0 when dim
+ * is a multiple of F*omega, as Table 2 prints).  Returns -1 on non-positive input. */
+int32_t pcsr_mac_job_gap(int32_t dim, int32_t F, int32_t omega);
+
+/* Static, never-freed description of an error code. */
+const char *pcsr_strerror(int code);
+
+/* hipError_t value of the last failing HIP call seen by this thread (0 if none). */
+int pcsr_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCSR_H */

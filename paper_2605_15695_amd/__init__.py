@@ -1,0 +1,10 @@
+"""PCSR SpMM for AMD MI355X: Python face of the C-ABI library libpcsr.so.
+
+The library is loaded on first use and there is no fallback: a missing or unloadable
+libpcsr.so raises.  `synth` holds the seeded input generators used by tests and bench.
+"""
+from .binding import (FEATURE_NAMES, PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_HOST_ONLY,  # noqa: F401
+                      PCSR_FLAG_NO_VALIDATE, PCSR_FLAG_NO_XCD_REMAP, Handle, PcsrError, make_params,
+                      pcsr_build, pcsr_export, pcsr_features, pcsr_free, pcsr_mac_job_gap,
+                      pcsr_params_t, pcsr_query_launch, pcsr_select, pcsr_set_kernel_params,
+                      pcsr_spmm, pcsr_strerror)

@@ -1,0 +1,215 @@
+"""Thin ctypes binding of libpcsr.so: argument marshalling only, same names as the C ABI.
+
+Every step of the path runs inside the library.  torch is used by callers for device
+memory and streams; this module only reads `data_ptr()` / `cuda_stream` from them.
+"""
+from __future__ import annotations
+
+import ctypes
+import pathlib
+
+import numpy as np
+
+_PKG = pathlib.Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libpcsr.so"
+
+PCSR_OK = 0
+PCSR_E_INVALID_ARG, PCSR_E_BAD_CSR, PCSR_E_UNSUPPORTED = -1, -2, -3
+PCSR_E_TOO_LARGE, PCSR_E_OOM, PCSR_E_HIP = -4, -5, -6
+PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_NO_VALIDATE, PCSR_FLAG_NO_XCD_REMAP, PCSR_FLAG_HOST_ONLY = 1, 2, 4, 8
+PCSR_N_FEATURES = 16
+FEATURE_NAMES = ("n", "n_hat", "nnz", "delta", "d", "d_hat", "d_max", "CV", "CV_hat",
+                 "SR_1", "SR_2", "rho", "b", "b_max", "PR_1", "PR_2")
+
+
+class pcsr_params_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("V", "S", "SG", "omega", "lanes_per_row", "vec", "rep", "waves_per_wg", "flags")]
+    _fields_ += [("reserved", ctypes.c_int32 * 3)]
+
+
+class PcsrError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = _lib().pcsr_strerror(code).decode()
+        if code == PCSR_E_HIP:
+            msg += f" (hipError {_lib().pcsr_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        if not LIB_PATH.exists():
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_15695_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(str(LIB_PATH))
+        i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+        pp = ctypes.POINTER(pcsr_params_t)
+        lib.pcsr_build.argtypes = [i64, i64, i64, vp, vp, vp, pp, ctypes.POINTER(vp)]
+        lib.pcsr_spmm.argtypes = [vp, vp, vp, i32, vp]
+        lib.pcsr_free.argtypes = [vp]
+        lib.pcsr_set_kernel_params.argtypes = [vp, i32, i32, i32, i32, i32]
+        lib.pcsr_query_launch.argtypes = [vp, i32, ctypes.POINTER(i32 * 6)]
+        lib.pcsr_export.argtypes = [vp, ctypes.POINTER(i64 * 6), vp, vp, vp, vp]
+        lib.pcsr_features.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32]
+        lib.pcsr_select.argtypes = [vp, i32, pp]
+        lib.pcsr_mac_job_gap.argtypes = [i32, i32, i32]
+        lib.pcsr_mac_job_gap.restype = i32
+        lib.pcsr_strerror.argtypes = [ctypes.c_int]
+        lib.pcsr_strerror.restype = ctypes.c_char_p
+        lib.pcsr_last_hip_error.restype = ctypes.c_int
+        for name in ("pcsr_build", "pcsr_spmm", "pcsr_free", "pcsr_set_kernel_params",
+                     "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select"):
+            getattr(lib, name).restype = ctypes.c_int
+        _LIB = lib
+    return _LIB
+
+
+def _ptr(a, dtype=None):
+    """Address of a numpy array or torch tensor (contiguous, right dtype); (keepalive, ptr, is_device)."""
+    if a is None:
+        return None, None, False
+    if isinstance(a, np.ndarray):
+        if dtype is not None and a.dtype != dtype:
+            a = a.astype(dtype)
+        a = np.ascontiguousarray(a)
+        return a, a.ctypes.data, False
+    # torch tensor
+    if not a.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if dtype is not None and np.dtype(str(a.dtype).replace("torch.", "")) != dtype:
+        raise ValueError(f"tensor dtype {a.dtype} != {dtype}")
+    return a, a.data_ptr(), a.is_cuda
+
+
+def make_params(V=1, S=0, SG=0, omega=0, lanes_per_row=0, vec=0, rep=0, waves_per_wg=0, flags=0):
+    p = pcsr_params_t()
+    p.V, p.S, p.SG, p.omega = V, int(S), SG, omega
+    p.lanes_per_row, p.vec, p.rep, p.waves_per_wg, p.flags = lanes_per_row, vec, rep, waves_per_wg, flags
+    return p
+
+
+class Handle:
+    """Owns a pcsr_handle_t; freed on close() or garbage collection."""
+
+    def __init__(self, raw, n_rows, n_cols):
+        self.raw = raw
+        self.n_rows, self.n_cols = n_rows, n_cols
+
+    def close(self):
+        if self.raw:
+            pcsr_free(self)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def pcsr_build(n_rows, n_cols, rowptr, colidx, vals, params=None) -> Handle:
+    k0, p_r, dev_r = _ptr(rowptr, np.dtype(np.int32))
+    k1, p_c, dev_c = _ptr(colidx, np.dtype(np.int32))
+    k2, p_v, dev_v = _ptr(vals, np.dtype(np.float32))
+    nnz = int(k1.shape[0]) if k1 is not None else 0
+    if int(k0.shape[0]) != n_rows + 1:
+        raise ValueError("rowptr must have n_rows + 1 entries")
+    if k2 is not None and int(k2.shape[0]) != nnz:
+        raise ValueError("vals and colidx differ in length")
+    p = params if params is not None else make_params()
+    if dev_r or dev_c or dev_v:
+        if not (dev_r and dev_c and dev_v):
+            raise ValueError("CSR arrays must be all host or all device")
+        p.flags |= PCSR_FLAG_DEVICE_CSR
+    out = ctypes.c_void_p()
+    rc = _lib().pcsr_build(n_rows, n_cols, nnz, p_r, p_c, p_v, ctypes.byref(p), ctypes.byref(out))
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_build")
+    return Handle(out.value, n_rows, n_cols)
+
+
+def pcsr_spmm(h: Handle, B, C, K: int, stream=None) -> None:
+    """B, C: torch device tensors (fp32, contiguous).  stream: torch.cuda.Stream, raw handle or None."""
+    _, p_b, dev_b = _ptr(B, np.dtype(np.float32))
+    _, p_c, dev_c = _ptr(C, np.dtype(np.float32))
+    if not (dev_b and dev_c):
+        raise ValueError("B and C must be device tensors")
+    if B.numel() != h.n_cols * K or C.numel() != h.n_rows * K:
+        raise ValueError("B must be n_cols x K and C n_rows x K")
+    s = getattr(stream, "cuda_stream", stream)
+    rc = _lib().pcsr_spmm(h.raw, p_b, p_c, K, s)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_spmm")
+
+
+def pcsr_free(h: Handle) -> None:
+    raw, h.raw = h.raw, None
+    rc = _lib().pcsr_free(raw)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_free")
+
+
+def pcsr_set_kernel_params(h: Handle, lanes_per_row=0, vec=0, rep=0, waves_per_wg=0, flags=0) -> None:
+    rc = _lib().pcsr_set_kernel_params(h.raw, lanes_per_row, vec, rep, waves_per_wg, flags)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_set_kernel_params")
+
+
+def pcsr_query_launch(h: Handle, K: int) -> dict:
+    out = (ctypes.c_int32 * 6)()
+    rc = _lib().pcsr_query_launch(h.raw, K, ctypes.byref(out))
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_query_launch")
+    return dict(zip(("lanes_per_row", "vec", "rep", "waves_per_wg", "grid_x", "grid_y"), list(out)))
+
+
+def pcsr_export(h: Handle) -> dict:
+    sizes = (ctypes.c_int64 * 6)()
+    rc = _lib().pcsr_export(h.raw, ctypes.byref(sizes), None, None, None, None)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_export")
+    P, M, nnz_v, V, SG, has_trow = list(sizes)
+    rowptr = np.empty(M + 1, np.int32)
+    colidx = np.empty(nnz_v, np.int32)
+    val = np.empty(nnz_v * V, np.float32)
+    trow = np.empty(M if has_trow else 0, np.int32)
+    rc = _lib().pcsr_export(h.raw, ctypes.byref(sizes), rowptr.ctypes.data, colidx.ctypes.data,
+                            val.ctypes.data, trow.ctypes.data if has_trow else None)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_export")
+    return dict(P=P, M=M, nnz_v=nnz_v, V=V, SG=SG, rowptr=rowptr, colidx=colidx, val=val, trow=trow)
+
+
+def pcsr_features(n_rows, n_cols, rowptr, colidx, omega=0) -> np.ndarray:
+    k0, p_r, _ = _ptr(rowptr, np.dtype(np.int32))
+    k1, p_c, _ = _ptr(colidx, np.dtype(np.int32))
+    out = np.empty(PCSR_N_FEATURES, np.float64)
+    rc = _lib().pcsr_features(n_rows, n_cols, int(k1.shape[0]), p_r, p_c, omega, out.ctypes.data,
+                              PCSR_N_FEATURES)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_features")
+    return out
+
+
+def pcsr_select(features, K: int) -> pcsr_params_t:
+    f = np.ascontiguousarray(features, dtype=np.float64)
+    if f.shape[0] < PCSR_N_FEATURES:
+        raise ValueError("features too short")
+    p = pcsr_params_t()
+    rc = _lib().pcsr_select(f.ctypes.data, K, ctypes.byref(p))
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_select")
+    return p
+
+
+def pcsr_mac_job_gap(dim: int, F: int, omega: int) -> int:
+    return int(_lib().pcsr_mac_job_gap(dim, F, omega))
+
+
+def pcsr_strerror(code: int) -> str:
+    return _lib().pcsr_strerror(code).decode()

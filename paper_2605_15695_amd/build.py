@@ -1,0 +1,44 @@
+"""Builds libpcsr.so (gfx950) in-tree with hipcc.  `python -m paper_2605_15695_amd.build`."""
+from __future__ import annotations
+
+import concurrent.futures
+import pathlib
+import subprocess
+
+PKG = pathlib.Path(__file__).resolve().parent
+CSRC = PKG / "csrc"
+OBJ = PKG / "_build"
+LIB = PKG / "libpcsr.so"
+
+HIPCC = "/opt/rocm/bin/hipcc"
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument"]
+# fp32 atomics as hardware instructions; packed fp32 instructions disabled
+DEVICE = ["--offload-arch=gfx950", "-munsafe-fp-atomics",
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+SOURCES = ["pcsr_kernels.hip", "pcsr_api.cpp", "pcsr_host.cpp"]
+
+
+def _compile(src: str) -> pathlib.Path:
+    obj = OBJ / (src + ".o")
+    cmd = [HIPCC, *COMMON]
+    if src.endswith(".hip"):
+        cmd += DEVICE
+    cmd += ["-c", str(CSRC / src), "-o", str(obj)]
+    subprocess.run(cmd, check=True, stderr=subprocess.PIPE, text=True)
+    return obj
+
+
+def build(verbose: bool = False) -> pathlib.Path:
+    OBJ.mkdir(exist_ok=True)
+    with concurrent.futures.ThreadPoolExecutor(max_workers=4) as ex:
+        objs = list(ex.map(_compile, SOURCES))
+    cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", *map(str, objs), "-o", str(LIB),
+           "-lpthread"]
+    subprocess.run(cmd, check=True)
+    if verbose:
+        print(LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(verbose=True)

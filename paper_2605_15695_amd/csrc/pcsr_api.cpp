@@ -1,0 +1,374 @@
+// C ABI of the PCSR SpMM library (see include/pcsr.h for the contract of each call).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/pcsr.h"
+#include "pcsr_host.h"
+#include "pcsr_kernels.h"
+
+namespace {
+
+constexpr uint32_t kMagic = 0x50435352u; // "PCSR"
+
+thread_local int g_last_hip = 0;
+
+inline bool hip_ok(hipError_t e)
+{
+    if (e == hipSuccess) return true;
+    g_last_hip = (int)e;
+    (void)hipGetLastError(); // clear the sticky error so later calls are not blamed
+    return false;
+}
+
+inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+int check_kernel_params(int lpr, int vec, int rep, int waves)
+{
+    if (lpr != 0 && !(is_pow2(lpr) && lpr >= 4 && lpr <= 64)) return PCSR_E_UNSUPPORTED;
+    if (vec != 0 && vec != 1 && vec != 2 && vec != 4) return PCSR_E_UNSUPPORTED;
+    if (rep != 0 && rep != 1 && rep != 2 && rep != 4) return PCSR_E_UNSUPPORTED;
+    if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return PCSR_E_UNSUPPORTED;
+    return PCSR_OK;
+}
+
+} // namespace
+
+struct pcsr_handle_s {
+    uint32_t magic = kMagic;
+    pcsr::HostPcsr host; // arrays kept only for host-only handles; scalars always valid
+    bool host_only = false;
+    int device = -1;
+    int32_t *d_rowptr = nullptr;
+    int32_t *d_colidx = nullptr;
+    float *d_val = nullptr;
+    int32_t *d_trow = nullptr;
+    int32_t *d_split = nullptr;
+    int64_t n_split = 0;
+    int32_t lpr = 0, vec = 0, rep = 0, waves = 0, flags = 0;
+};
+
+namespace {
+
+inline bool valid(pcsr_handle_t h) { return h && h->magic == kMagic; }
+
+void release_device(pcsr_handle_t h)
+{
+    if (h->d_rowptr) (void)hipFree(h->d_rowptr);
+    if (h->d_colidx) (void)hipFree(h->d_colidx);
+    if (h->d_val) (void)hipFree(h->d_val);
+    if (h->d_trow) (void)hipFree(h->d_trow);
+    if (h->d_split) (void)hipFree(h->d_split);
+    h->d_rowptr = h->d_colidx = h->d_trow = h->d_split = nullptr;
+    h->d_val = nullptr;
+}
+
+template <class T> int upload(const std::vector<T> &src, T **dst)
+{
+    *dst = nullptr;
+    // one spare element so empty arrays still have a valid device address
+    size_t bytes = (src.size() + 1) * sizeof(T);
+    hipError_t e = hipMalloc((void **)dst, bytes);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        return PCSR_E_OOM;
+    }
+    if (!hip_ok(e)) return PCSR_E_HIP;
+    if (!src.empty() && !hip_ok(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice)))
+        return PCSR_E_HIP;
+    return PCSR_OK;
+}
+
+// Launch shape for width K under the handle's kernel parameters ("0 = auto" resolved).
+int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
+{
+    if (K <= 0) return PCSR_E_UNSUPPORTED;
+    int vec = h->vec ? h->vec : (K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1));
+    if (K % vec != 0) return PCSR_E_UNSUPPORTED;
+    int lpr = h->lpr;
+    if (!lpr) {
+        int need = (K + vec - 1) / vec;
+        lpr = 4;
+        while (lpr < need && lpr < 64) lpr <<= 1;
+    }
+    int rep = h->rep;
+    if (!rep) {
+        int need = (K + lpr * vec - 1) / (lpr * vec);
+        rep = 1;
+        while (rep < need && rep < 4) rep <<= 1;
+    }
+    int waves = h->waves ? h->waves : 4;
+    if (!pcsr::kernel_exists(h->host.V, h->host.S, lpr, vec, rep)) return PCSR_E_UNSUPPORTED;
+    const int64_t items_per_wg = (int64_t)waves * (64 / lpr);
+    const int64_t gx = (h->host.M + items_per_wg - 1) / items_per_wg;
+    const int64_t tile = (int64_t)lpr * vec * rep;
+    const int64_t gy = (K + tile - 1) / tile;
+    if (gx > 0x7fffffffLL || gy > 65535) return PCSR_E_TOO_LARGE;
+    ls->lpr = lpr;
+    ls->vec = vec;
+    ls->rep = rep;
+    ls->waves = waves;
+    ls->grid_x = (int32_t)gx;
+    ls->grid_y = (int32_t)gy;
+    return PCSR_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+               const int32_t *colidx, const float *vals, const pcsr_params_t *p,
+               pcsr_handle_t *out)
+{
+    if (!out || !rowptr || n_rows < 0 || n_cols < 0 || nnz < 0) return PCSR_E_INVALID_ARG;
+    if (nnz > 0 && (!colidx || !vals)) return PCSR_E_INVALID_ARG;
+    pcsr_params_t prm;
+    std::memset(&prm, 0, sizeof(prm));
+    if (p) prm = *p;
+    if (prm.V == 0) prm.V = 1;
+    if (prm.V != 1 && prm.V != 2) return PCSR_E_UNSUPPORTED;
+    if (prm.S != 0 && prm.S != 1) return PCSR_E_UNSUPPORTED;
+    if (prm.SG < 0 || prm.omega < 0) return PCSR_E_INVALID_ARG;
+    if (prm.reserved[0] || prm.reserved[1] || prm.reserved[2]) return PCSR_E_INVALID_ARG;
+    if (nnz >= (int64_t(1) << 31) || n_rows >= (int64_t(1) << 31) - 1 || n_cols >= (int64_t(1) << 31))
+        return PCSR_E_TOO_LARGE;
+    int rc = check_kernel_params(prm.lanes_per_row, prm.vec, prm.rep, prm.waves_per_wg);
+    if (rc != PCSR_OK) return rc;
+    const bool host_only = (prm.flags & PCSR_FLAG_HOST_ONLY) != 0;
+    if (host_only && (prm.flags & PCSR_FLAG_DEVICE_CSR)) return PCSR_E_INVALID_ARG;
+
+    try {
+        // CSR arrays handed over in device memory are staged on the host first
+        std::vector<int32_t> s_rowptr, s_colidx;
+        std::vector<float> s_vals;
+        if (prm.flags & PCSR_FLAG_DEVICE_CSR) {
+            s_rowptr.resize(n_rows + 1);
+            s_colidx.resize(nnz);
+            s_vals.resize(nnz);
+            if (!hip_ok(hipMemcpy(s_rowptr.data(), rowptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToHost)))
+                return PCSR_E_HIP;
+            if (nnz && !hip_ok(hipMemcpy(s_colidx.data(), colidx, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost)))
+                return PCSR_E_HIP;
+            if (nnz && !hip_ok(hipMemcpy(s_vals.data(), vals, sizeof(float) * nnz, hipMemcpyDeviceToHost)))
+                return PCSR_E_HIP;
+            rowptr = s_rowptr.data();
+            colidx = s_colidx.data();
+            vals = s_vals.data();
+        }
+        if (!(prm.flags & PCSR_FLAG_NO_VALIDATE)) {
+            rc = pcsr::validate_csr(n_rows, n_cols, nnz, rowptr, colidx);
+            if (rc != PCSR_OK) return rc;
+        } else if (rowptr[0] != 0 || rowptr[n_rows] != nnz) {
+            return PCSR_E_BAD_CSR;
+        }
+
+        pcsr_handle_s *h = new pcsr_handle_s();
+        rc = pcsr::build_host(n_rows, n_cols, nnz, rowptr, colidx, vals, prm.V, prm.S, prm.SG,
+                              prm.omega, &h->host);
+        if (rc != PCSR_OK) {
+            delete h;
+            return rc;
+        }
+        h->host_only = host_only;
+        h->lpr = prm.lanes_per_row;
+        h->vec = prm.vec;
+        h->rep = prm.rep;
+        h->waves = prm.waves_per_wg;
+        h->flags = prm.flags;
+        h->n_split = (int64_t)h->host.split_panels.size();
+        if (!host_only) {
+            if (!hip_ok(hipGetDevice(&h->device))) {
+                delete h;
+                return PCSR_E_HIP;
+            }
+            rc = upload(h->host.rowptr, &h->d_rowptr);
+            if (rc == PCSR_OK) rc = upload(h->host.colidx, &h->d_colidx);
+            if (rc == PCSR_OK) rc = upload(h->host.val, &h->d_val);
+            if (rc == PCSR_OK && h->host.S) rc = upload(h->host.trow, &h->d_trow);
+            if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_panels, &h->d_split);
+            if (rc != PCSR_OK) {
+                release_device(h);
+                delete h;
+                return rc;
+            }
+            // the device copies are the product; drop the host staging arrays
+            std::vector<int32_t>().swap(h->host.rowptr);
+            std::vector<int32_t>().swap(h->host.colidx);
+            std::vector<float>().swap(h->host.val);
+            std::vector<int32_t>().swap(h->host.trow);
+            std::vector<int32_t>().swap(h->host.split_panels);
+        }
+        *out = h;
+        return PCSR_OK;
+    } catch (const std::bad_alloc &) {
+        return PCSR_E_OOM;
+    }
+}
+
+int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream)
+{
+    if (!valid(h)) return PCSR_E_INVALID_ARG;
+    if (h->host_only) return PCSR_E_UNSUPPORTED;
+    if (K <= 0) return PCSR_E_UNSUPPORTED;
+    if (!C && h->host.n_rows > 0) return PCSR_E_INVALID_ARG;
+    if (!B && h->host.n_cols > 0 && h->host.nnz_v > 0) return PCSR_E_INVALID_ARG;
+    pcsr::LaunchShape ls;
+    int rc = resolve_launch(h, K, &ls);
+    if (rc != PCSR_OK) return rc;
+    const uintptr_t align = 4u * (unsigned)ls.vec;
+    if ((reinterpret_cast<uintptr_t>(B) % align) || (reinterpret_cast<uintptr_t>(C) % align))
+        return PCSR_E_INVALID_ARG;
+    if (h->host.n_rows == 0) return PCSR_OK;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (h->host.S && h->n_split > 0) {
+        if (!hip_ok(pcsr::launch_zero_panels(h->d_split, h->n_split, h->host.V, C,
+                                             (int32_t)h->host.n_rows, K, s)))
+            return PCSR_E_HIP;
+    }
+    pcsr::SpmmArgs a;
+    a.rowptr = h->d_rowptr;
+    a.colidx = h->d_colidx;
+    a.val = h->d_val;
+    a.trow = h->d_trow;
+    a.B = B;
+    a.C = C;
+    a.M = (int32_t)h->host.M;
+    a.n_rows = (int32_t)h->host.n_rows;
+    a.K = K;
+    a.nblk = ls.grid_x;
+    a.xcd_remap = (h->flags & PCSR_FLAG_NO_XCD_REMAP) ? 0 : 1;
+    if (!hip_ok(pcsr::launch_spmm(h->host.V, h->host.S, ls, a, s))) return PCSR_E_HIP;
+    return PCSR_OK;
+}
+
+int pcsr_free(pcsr_handle_t h)
+{
+    if (!h) return PCSR_OK;
+    if (!valid(h)) return PCSR_E_INVALID_ARG;
+    release_device(h);
+    h->magic = 0;
+    delete h;
+    return PCSR_OK;
+}
+
+int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, int32_t rep,
+                           int32_t waves_per_wg, int32_t flags)
+{
+    if (!valid(h)) return PCSR_E_INVALID_ARG;
+    int rc = check_kernel_params(lanes_per_row, vec, rep, waves_per_wg);
+    if (rc != PCSR_OK) return rc;
+    h->lpr = lanes_per_row;
+    h->vec = vec;
+    h->rep = rep;
+    h->waves = waves_per_wg;
+    h->flags = (h->flags & ~PCSR_FLAG_NO_XCD_REMAP) | (flags & PCSR_FLAG_NO_XCD_REMAP);
+    return PCSR_OK;
+}
+
+int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[6])
+{
+    if (!valid(h) || !out) return PCSR_E_INVALID_ARG;
+    pcsr::LaunchShape ls;
+    int rc = resolve_launch(h, K, &ls);
+    if (rc != PCSR_OK) return rc;
+    out[0] = ls.lpr;
+    out[1] = ls.vec;
+    out[2] = ls.rep;
+    out[3] = ls.waves;
+    out[4] = ls.grid_x;
+    out[5] = ls.grid_y;
+    return PCSR_OK;
+}
+
+int pcsr_export(pcsr_handle_t h, int64_t sizes[6], int32_t *rowptr, int32_t *colidx, float *val,
+                int32_t *trow)
+{
+    if (!valid(h)) return PCSR_E_INVALID_ARG;
+    const pcsr::HostPcsr &m = h->host;
+    if (sizes) {
+        sizes[0] = m.P;
+        sizes[1] = m.M;
+        sizes[2] = m.nnz_v;
+        sizes[3] = m.V;
+        sizes[4] = m.SG;
+        sizes[5] = m.S ? 1 : 0;
+    }
+    auto fetch = [&](void *dst, const void *host_src, const void *dev_src, size_t bytes) -> int {
+        if (!dst || bytes == 0) return PCSR_OK;
+        if (h->host_only) {
+            std::memcpy(dst, host_src, bytes);
+            return PCSR_OK;
+        }
+        return hip_ok(hipMemcpy(dst, dev_src, bytes, hipMemcpyDeviceToHost)) ? PCSR_OK : PCSR_E_HIP;
+    };
+    int rc = fetch(rowptr, m.rowptr.data(), h->d_rowptr, sizeof(int32_t) * (m.M + 1));
+    if (rc == PCSR_OK) rc = fetch(colidx, m.colidx.data(), h->d_colidx, sizeof(int32_t) * m.nnz_v);
+    if (rc == PCSR_OK) rc = fetch(val, m.val.data(), h->d_val, sizeof(float) * m.nnz_v * m.V);
+    if (rc == PCSR_OK && m.S) rc = fetch(trow, m.trow.data(), h->d_trow, sizeof(int32_t) * m.M);
+    return rc;
+}
+
+int pcsr_features(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                  const int32_t *colidx, int32_t omega, double *out, int32_t n_out)
+{
+    if (!out || n_out < PCSR_N_FEATURES || !rowptr || omega < 0) return PCSR_E_INVALID_ARG;
+    int rc = pcsr::validate_csr(n_rows, n_cols, nnz, rowptr, colidx);
+    if (rc != PCSR_OK) return rc;
+    try {
+        return pcsr::features_host(n_rows, n_cols, nnz, rowptr, colidx, omega, out);
+    } catch (const std::bad_alloc &) {
+        return PCSR_E_OOM;
+    }
+}
+
+int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
+{
+    if (!f || !out) return PCSR_E_INVALID_ARG;
+    if (K <= 0) return PCSR_E_UNSUPPORTED;
+    pcsr_params_t p;
+    std::memset(&p, 0, sizeof(p));
+    const double d_hat = f[5], d_max = f[6], cv = f[7], pr2 = f[15];
+    // Balancing pays when a few rows dwarf the average one (Section 3.2): the longest
+    // row would keep one group busy long after the rest of the grid has drained.
+    p.S = (d_max > 32.0 * std::fmax(d_hat, 1.0) && cv > 1.0) ? 1 : 0;
+    // Vector size 2 pays only when adjacent rows share most columns (Table 1: wins at
+    // about 30 % padding, loses near 50 %).
+    p.V = (pr2 < 0.35 && d_hat >= 4.0) ? 2 : 1;
+    p.SG = 0;
+    p.omega = 64;
+    // kernel parameters: left on auto (resolved from K at launch)
+    *out = p;
+    return PCSR_OK;
+}
+
+int32_t pcsr_mac_job_gap(int32_t dim, int32_t F, int32_t omega)
+{
+    if (dim <= 0 || F <= 0 || omega <= 0) return -1;
+    const int64_t span = (int64_t)F * omega;
+    const int64_t tn = dim < span ? dim : span;
+    const int64_t tr = dim % span;
+    return tr == 0 ? 0 : (int32_t)(tn - tr);
+}
+
+const char *pcsr_strerror(int code)
+{
+    switch (code) {
+    case PCSR_OK: return "ok";
+    case PCSR_E_INVALID_ARG: return "invalid argument";
+    case PCSR_E_BAD_CSR: return "malformed CSR (rowptr not monotone, column out of range, unsorted or duplicate columns)";
+    case PCSR_E_UNSUPPORTED: return "unsupported parameter value";
+    case PCSR_E_TOO_LARGE: return "size does not fit 32-bit indexing";
+    case PCSR_E_OOM: return "out of memory";
+    case PCSR_E_HIP: return "HIP runtime error";
+    }
+    return "unknown error";
+}
+
+int pcsr_last_hip_error(void) { return g_last_hip; }
+
+} // extern "C"

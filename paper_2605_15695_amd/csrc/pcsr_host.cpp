@@ -1,0 +1,265 @@
+// Host-side PCSR generation (Section 4.2, "PCSR Generation") and the matrix features
+// of Table 3.  Plain C++ with std::thread; no GPU calls here.
+#include "pcsr_host.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <thread>
+
+#include "../../include/pcsr.h"
+
+namespace pcsr {
+namespace {
+
+template <class F> void parallel_for(int64_t n, int64_t grain, F &&fn)
+{
+    if (n <= 0) return;
+    unsigned hw = std::thread::hardware_concurrency();
+    int64_t nt = std::max<int64_t>(1, std::min<int64_t>(hw ? hw : 4, 16));
+    nt = std::min<int64_t>(nt, (n + grain - 1) / grain);
+    if (nt <= 1) {
+        fn(int64_t(0), n);
+        return;
+    }
+    std::vector<std::thread> th;
+    th.reserve(nt);
+    int64_t per = (n + nt - 1) / nt;
+    for (int64_t t = 0; t < nt; ++t) {
+        int64_t lo = t * per, hi = std::min(n, lo + per);
+        if (lo >= hi) break;
+        th.emplace_back([=, &fn] { fn(lo, hi); });
+    }
+    for (auto &t : th) t.join();
+}
+
+inline int64_t ceildiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Number of distinct columns in the union of rows r0 and r0+1 (the second may be absent).
+inline int64_t union_count(const int32_t *rowptr, const int32_t *colidx, int64_t r0, int64_t n_rows)
+{
+    int64_t a = rowptr[r0], ae = rowptr[r0 + 1];
+    if (r0 + 1 >= n_rows) return ae - a;
+    int64_t b = ae, be = rowptr[r0 + 2], cnt = 0;
+    while (a < ae && b < be) {
+        int32_t ca = colidx[a], cb = colidx[b];
+        a += (ca <= cb);
+        b += (cb <= ca);
+        ++cnt;
+    }
+    return cnt + (ae - a) + (be - b);
+}
+
+// Eq. (3): SG = ceil(avg vectors per non-empty panel / omega) * omega, in exact integers.
+inline int64_t eq3_sg(int64_t nnz_v, int64_t nonempty, int64_t omega)
+{
+    if (nnz_v == 0 || nonempty == 0) return omega;
+    return ceildiv(nnz_v, nonempty * omega) * omega;
+}
+
+} // namespace
+
+int validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                 const int32_t *colidx)
+{
+    if (n_rows < 0 || n_cols < 0 || nnz < 0) return PCSR_E_INVALID_ARG;
+    if (nnz >= (int64_t(1) << 31) || n_rows >= (int64_t(1) << 31) - 1 || n_cols >= (int64_t(1) << 31))
+        return PCSR_E_TOO_LARGE;
+    if (!rowptr || (nnz > 0 && !colidx)) return PCSR_E_INVALID_ARG;
+    if (rowptr[0] != 0 || rowptr[n_rows] != nnz) return PCSR_E_BAD_CSR;
+    std::atomic<int> bad{0};
+    parallel_for(n_rows, 1 << 14, [&](int64_t lo, int64_t hi) {
+        for (int64_t i = lo; i < hi; ++i) {
+            int64_t s = rowptr[i], e = rowptr[i + 1];
+            if (s > e || s < 0 || e > nnz) {
+                bad = 1;
+                return;
+            }
+            int64_t prev = -1;
+            for (int64_t p = s; p < e; ++p) {
+                int64_t c = colidx[p];
+                if (c <= prev || c >= n_cols) {
+                    bad = 1;
+                    return;
+                }
+                prev = c;
+            }
+        }
+    });
+    return bad ? PCSR_E_BAD_CSR : PCSR_OK;
+}
+
+int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+               const int32_t *colidx, const float *vals, int32_t V, int32_t S, int32_t SG,
+               int32_t omega, HostPcsr *out)
+{
+    if (V != 1 && V != 2) return PCSR_E_UNSUPPORTED;
+    if (SG < 0 || omega < 0) return PCSR_E_INVALID_ARG;
+    if (omega == 0) omega = 64;
+    try {
+        HostPcsr &h = *out;
+        h.n_rows = n_rows;
+        h.n_cols = n_cols;
+        h.nnz = nnz;
+        h.V = V;
+        h.S = S ? 1 : 0;
+        const int64_t P = ceildiv(n_rows, V);
+        h.P = P;
+
+        // ---- vectorised blocking: panel row pointer, then column / value fill
+        std::vector<int32_t> prow(P + 1);
+        prow[0] = 0;
+        if (V == 1) {
+            std::memcpy(prow.data(), rowptr, sizeof(int32_t) * (n_rows + 1));
+            h.nnz_v = nnz;
+            h.colidx.assign(colidx, colidx + nnz);
+            h.val.assign(vals, vals + nnz);
+        } else {
+            std::vector<int32_t> cnt(P);
+            parallel_for(P, 1 << 13, [&](int64_t lo, int64_t hi) {
+                for (int64_t p = lo; p < hi; ++p)
+                    cnt[p] = (int32_t)union_count(rowptr, colidx, 2 * p, n_rows);
+            });
+            int64_t run = 0;
+            for (int64_t p = 0; p < P; ++p) {
+                run += cnt[p];
+                prow[p + 1] = (int32_t)run;
+            }
+            h.nnz_v = run;
+            h.colidx.resize(run);
+            h.val.resize(run * 2);
+            parallel_for(P, 1 << 13, [&](int64_t lo, int64_t hi) {
+                for (int64_t p = lo; p < hi; ++p) {
+                    int64_t r0 = 2 * p;
+                    int64_t a = rowptr[r0], ae = rowptr[r0 + 1];
+                    int64_t b = ae, be = (r0 + 1 < n_rows) ? rowptr[r0 + 2] : ae;
+                    int64_t o = prow[p];
+                    while (a < ae || b < be) {
+                        int32_t ca = a < ae ? colidx[a] : INT32_MAX;
+                        int32_t cb = b < be ? colidx[b] : INT32_MAX;
+                        int32_t c = std::min(ca, cb);
+                        h.colidx[o] = c;
+                        h.val[2 * o] = (ca == c) ? vals[a] : 0.0f;
+                        h.val[2 * o + 1] = (cb == c) ? vals[b] : 0.0f;
+                        a += (ca == c);
+                        b += (cb == c);
+                        ++o;
+                    }
+                }
+            });
+        }
+
+        // ---- split granularity (Eq. 3) is reported even when S is off
+        int64_t nonempty = 0;
+        for (int64_t p = 0; p < P; ++p) nonempty += (prow[p + 1] > prow[p]);
+        const int64_t sg = SG > 0 ? SG : eq3_sg(h.nnz_v, nonempty, omega);
+        if (sg >= (int64_t(1) << 31)) return PCSR_E_TOO_LARGE;
+        h.SG = (int32_t)sg;
+
+        if (!h.S) {
+            h.M = P;
+            h.rowptr.swap(prow);
+            h.trow.clear();
+            int64_t mx = 0;
+            for (int64_t p = 0; p < P; ++p) mx = std::max<int64_t>(mx, h.rowptr[p + 1] - h.rowptr[p]);
+            h.max_item_len = mx;
+            return PCSR_OK;
+        }
+
+        // ---- workload split: panel with l vectors -> max(1, ceil(l/SG)) items
+        std::vector<int64_t> first(P + 1);
+        first[0] = 0;
+        for (int64_t p = 0; p < P; ++p) {
+            int64_t l = prow[p + 1] - prow[p];
+            int64_t items = std::max<int64_t>(1, ceildiv(l, sg));
+            first[p + 1] = first[p] + items;
+            if (items > 1) h.split_panels.push_back((int32_t)p);
+        }
+        const int64_t M = first[P];
+        if (M >= (int64_t(1) << 31) - 1) return PCSR_E_TOO_LARGE;
+        h.M = M;
+        h.rowptr.resize(M + 1);
+        h.trow.resize(M);
+        parallel_for(P, 1 << 14, [&](int64_t lo, int64_t hi) {
+            for (int64_t p = lo; p < hi; ++p) {
+                int64_t start = prow[p];
+                for (int64_t it = first[p]; it < first[p + 1]; ++it) {
+                    h.rowptr[it] = (int32_t)start;
+                    h.trow[it] = (int32_t)p;
+                    start += sg;
+                }
+            }
+        });
+        h.rowptr[M] = (int32_t)h.nnz_v;
+        h.max_item_len = std::min<int64_t>(sg, h.nnz_v);
+        return PCSR_OK;
+    } catch (const std::bad_alloc &) {
+        return PCSR_E_OOM;
+    }
+}
+
+int features_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                  const int32_t *colidx, int32_t omega, double *out)
+{
+    if (omega == 0) omega = 64;
+    if (omega < 0) return PCSR_E_INVALID_ARG;
+    int64_t n_hat = 0, d_max = 0, nnz2 = 0, nonempty2 = 0;
+    double bw_sum = 0.0, bw_max = 0.0;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        int64_t s = rowptr[i], e = rowptr[i + 1], l = e - s;
+        if (l > 0) {
+            ++n_hat;
+            d_max = std::max(d_max, l);
+            double bw = double(colidx[e - 1]) - double(colidx[s]);
+            bw_sum += bw;
+            bw_max = std::max(bw_max, bw);
+        }
+    }
+    const double d = n_rows ? double(nnz) / double(n_rows) : 0.0;
+    const double d_hat = n_hat ? double(nnz) / double(n_hat) : 0.0;
+    double ss = 0.0, ss_hat = 0.0;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        double l = double(rowptr[i + 1] - rowptr[i]);
+        ss += (l - d) * (l - d);
+        if (l > 0) ss_hat += (l - d_hat) * (l - d_hat);
+    }
+    const double cv = d > 0 ? std::sqrt(ss / double(n_rows)) / d : 0.0;
+    const double cv_hat = n_hat ? std::sqrt(ss_hat / double(n_hat)) / d_hat : 0.0;
+
+    // V = 2 panel lengths
+    const int64_t P2 = ceildiv(n_rows, 2);
+    std::vector<int32_t> len2(P2);
+    for (int64_t p = 0; p < P2; ++p) {
+        int64_t l = union_count(rowptr, colidx, 2 * p, n_rows);
+        len2[p] = (int32_t)l;
+        nnz2 += l;
+        nonempty2 += (l > 0);
+    }
+    const int64_t sg1 = eq3_sg(nnz, n_hat, omega), sg2 = eq3_sg(nnz2, nonempty2, omega);
+    int64_t M1 = 0, M2 = 0;
+    for (int64_t i = 0; i < n_rows; ++i)
+        M1 += std::max<int64_t>(1, ceildiv(rowptr[i + 1] - rowptr[i], sg1));
+    for (int64_t p = 0; p < P2; ++p) M2 += std::max<int64_t>(1, ceildiv(len2[p], sg2));
+
+    out[0] = double(n_rows);
+    out[1] = double(n_hat);
+    out[2] = double(nnz);
+    out[3] = n_rows ? double(n_hat) / double(n_rows) : 0.0;
+    out[4] = d;
+    out[5] = d_hat;
+    out[6] = double(d_max);
+    out[7] = cv;
+    out[8] = cv_hat;
+    out[9] = n_rows ? double(M1) / double(n_rows) : 1.0;
+    out[10] = P2 ? double(M2) / double(P2) : 1.0;
+    out[11] = (n_rows && n_cols) ? double(nnz) / (double(n_rows) * double(n_cols)) : 0.0;
+    out[12] = n_rows ? bw_sum / double(n_rows) : 0.0;
+    out[13] = bw_max;
+    out[14] = 0.0;
+    out[15] = nnz2 ? 1.0 - double(nnz) / (double(nnz2) * 2.0) : 0.0;
+    return PCSR_OK;
+}
+
+} // namespace pcsr

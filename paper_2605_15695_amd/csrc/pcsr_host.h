@@ -1,0 +1,38 @@
+// Host-side PCSR construction and matrix features (internal to the library).
+#pragma once
+#include <cstdint>
+#include <vector>
+
+namespace pcsr {
+
+// The four PCSR arrays of Section 4.2 plus the bookkeeping the launcher needs.
+struct HostPcsr {
+    int64_t n_rows = 0, n_cols = 0, nnz = 0;
+    int64_t P = 0;     // row panels = ceil(n_rows / V)
+    int64_t M = 0;     // work items (== P when S is off)
+    int64_t nnz_v = 0; // nonzero vectors
+    int32_t V = 1, S = 0, SG = 0;
+    std::vector<int32_t> rowptr; // M+1
+    std::vector<int32_t> colidx; // nnz_v
+    std::vector<float> val;      // nnz_v * V, padding slots +0.0f
+    std::vector<int32_t> trow;   // M when S, else empty
+    // Not part of the format: panels that own more than one work item.  Their C rows
+    // are cleared before the kernel accumulates into them.
+    std::vector<int32_t> split_panels;
+    int64_t max_item_len = 0;
+};
+
+// Returns PCSR_OK or PCSR_E_BAD_CSR / PCSR_E_TOO_LARGE / PCSR_E_INVALID_ARG.
+int validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                 const int32_t *colidx);
+
+// Vectorised blocking followed by the optional workload split.
+int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+               const int32_t *colidx, const float *vals, int32_t V, int32_t S, int32_t SG,
+               int32_t omega, HostPcsr *out);
+
+// Table 3 features in the order documented in pcsr.h.
+int features_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                  const int32_t *colidx, int32_t omega, double *out);
+
+} // namespace pcsr

@@ -1,0 +1,39 @@
+// Launchers of the HIP SpMM kernel family (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace pcsr {
+
+struct SpmmArgs {
+    const int32_t *rowptr; // M+1, device
+    const int32_t *colidx; // nnz_v, device
+    const float *val;      // nnz_v * V, device
+    const int32_t *trow;   // M (S only), device
+    const float *B;
+    float *C;
+    int32_t M;      // work items
+    int32_t n_rows; // rows of C
+    int32_t K;
+    int32_t nblk;      // grid.x
+    int32_t xcd_remap; // 1: contiguous item ranges per XCD
+};
+
+// Resolved launch shape.
+struct LaunchShape {
+    int32_t lpr, vec, rep, waves;
+    int32_t grid_x, grid_y;
+};
+
+bool kernel_exists(int V, int S, int lpr, int vec, int rep);
+
+// Enqueues the SpMM kernel <V,S,lpr,vec,rep> with `waves` wavefronts per workgroup.
+hipError_t launch_spmm(int V, int S, const LaunchShape &ls, const SpmmArgs &args,
+                       hipStream_t stream);
+
+// Clears the C rows of the listed panels (rows panel*V .. panel*V+V-1, K floats each).
+hipError_t launch_zero_panels(const int32_t *panels, int64_t n_panels, int V, float *C,
+                              int32_t n_rows, int32_t K, hipStream_t stream);
+
+} // namespace pcsr

@@ -1,0 +1,233 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle.
+
+Acceptance for every element: |C - C_ref| <= 1e-5 * sum_j |a_ij b_jk| + 1e-6.
+PCSR arrays read back from the device must equal the numpy format reference bit for bit.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2605_15695_amd as pc
+from oracle import pcsr_format as pf
+from paper_2605_15695_amd import synth
+from tests.helpers import random_csr
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-6
+
+
+def _spmm(g, B, params, K, prefill=float("nan"), stream=None, kernel=None):
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, params)
+    if kernel:
+        pc.pcsr_set_kernel_params(h, *kernel)
+    Bd = torch.from_numpy(B).cuda()
+    Cd = torch.full((g.n_rows, K), prefill, dtype=torch.float32, device="cuda")
+    pc.pcsr_spmm(h, Bd, Cd, K, stream)
+    torch.cuda.synchronize()
+    out = Cd.cpu().numpy()
+    h.close()
+    return out
+
+
+def _check(C, ref, bound, what=""):
+    ok, worst = oracle.within_tolerance(C, ref, bound, RTOL, ATOL)
+    assert ok, f"{what}: worst err/limit = {worst:.3g}"
+
+
+_ORACLE_CACHE = {}
+
+
+def _oracle(name, g, K, dist):
+    key = (name, K, dist)
+    if key not in _ORACLE_CACHE:
+        B = synth.dense_operand(g.n_cols, K, dist, 17 + K)
+        _ORACLE_CACHE[key] = (B,) + oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+    return _ORACLE_CACHE[key]
+
+
+_GRAPHS = {}
+
+
+def _graph(name):
+    if name not in _GRAPHS:
+        _GRAPHS[name] = synth.workload(name, "small")
+    return _GRAPHS[name]
+
+
+@pytest.mark.parametrize("name", list(synth.WORKLOADS))
+@pytest.mark.parametrize("V,S", [(1, 0), (1, 1), (2, 0), (2, 1)])
+def test_workloads_default_kernel(name, V, S):
+    g = _graph(name)
+    spec = synth.WORKLOADS[name]
+    for K in sorted(set(spec["K"]) | {16}):
+        B, ref, bound = _oracle(name, g, K, spec["B"])
+        print(f"case {name} V={V} S={S} K={K}", flush=True)
+        C = _spmm(g, B, pc.make_params(V=V, S=S), K)
+        _check(C, ref, bound, f"{name} V={V} S={S} K={K}")
+
+
+@pytest.mark.parametrize("V,S", [(1, 0), (1, 1), (2, 0), (2, 1)])
+def test_every_kernel_variant(V, S):
+    """All (lanes_per_row, vec, rep) instances, each at a K that needs two grid.y slices
+    with a ragged last slice, on a skewed graph with an odd row count."""
+    g0 = _graph("rmat20")
+    n = g0.n_rows - 1                       # odd: the last V=2 panel is short
+    nnz = int(g0.rowptr[n])
+    cols_ok = g0.colidx[:nnz] < n
+    # drop the last row and column so the matrix stays square
+    keep = np.nonzero(cols_ok)[0]
+    row_of = np.repeat(np.arange(n), np.diff(g0.rowptr[:n + 1]))[keep]
+    rowptr = np.zeros(n + 1, np.int32)
+    np.cumsum(np.bincount(row_of, minlength=n), out=rowptr[1:])
+    g = synth.Graph("rmat_odd", n, n, rowptr, g0.colidx[keep], g0.vals[keep])
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=S, SG=32))
+    waves_cycle = itertools.cycle([1, 2, 4, 8])
+    cache = {}
+    for lpr, vec, rep in itertools.product([4, 8, 16, 32, 64], [1, 2, 4], [1, 2, 4]):
+        K = lpr * vec * rep + vec * 3       # second slice covers 3 lanes' worth only
+        if K not in cache:
+            B = synth.dense_operand(n, K, "normal", K)
+            cache[K] = (torch.from_numpy(B).cuda(),) + oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+        Bd, ref, bound = cache[K]
+        waves = next(waves_cycle)
+        print(f"case V={V} S={S} lpr={lpr} vec={vec} rep={rep} waves={waves} K={K}", flush=True)
+        pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, pc.PCSR_FLAG_NO_XCD_REMAP if rep == 2 else 0)
+        q = pc.pcsr_query_launch(h, K)
+        assert q["grid_y"] == 2
+        Cd = torch.full((n, K), float("nan"), dtype=torch.float32, device="cuda")
+        pc.pcsr_spmm(h, Bd, Cd, K)
+        torch.cuda.synchronize()
+        _check(Cd.cpu().numpy(), ref, bound, f"V={V} S={S} lpr={lpr} vec={vec} rep={rep}")
+    h.close()
+
+
+def _tiny_cases():
+    rng = np.random.default_rng(3)
+    cases = {}
+    cases["n1"] = (1, 1, np.array([0, 1], np.int32), np.array([0], np.int32), np.array([2.5], np.float32))
+    cases["n1_empty"] = (1, 4, np.array([0, 0], np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    rp, ci, va, _ = random_csr(rng, 3, 5, 0.6)
+    cases["n3_rect"] = (3, 5, rp, ci, va)
+    rp, ci, va, _ = random_csr(rng, 37, 37, 0.2, empty_rows=(0, 1, 35, 36))
+    cases["empty_first_last"] = (37, 37, rp, ci, va)
+    rp, ci, va, _ = random_csr(rng, 9, 700, 0.01, full_rows=(4,))
+    cases["one_dense_row"] = (9, 700, rp, ci, va)
+    rp, ci, va, _ = random_csr(rng, 64, 300, 0.0, full_rows=(7, 8, 40))
+    cases["only_long_rows"] = (64, 300, rp, ci, va)
+    cases["all_empty"] = (10, 10, np.zeros(11, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    return cases
+
+
+@pytest.mark.parametrize("case", list(_tiny_cases()))
+def test_tiny_adversarial_all_tuples(case):
+    n_rows, n_cols, rp, ci, va = _tiny_cases()[case]
+    g = synth.Graph(case, n_rows, n_cols, rp, ci, va)
+    for K in (16, 20, 1):
+        B = synth.dense_operand(n_cols, K, "uniform", 5)
+        ref, bound = oracle.spmm(rp, ci, va, B)
+        for V, S, SG in [(1, 0, 0), (2, 0, 0), (1, 1, 0), (2, 1, 0), (1, 1, 3), (2, 1, 3), (1, 1, 64)]:
+            kernels = [None, (4, 0, 0, 1), (64, 0, 1, 2), (16, 1, 2, 8)]
+            for kern in kernels:
+                print(f"case {case} K={K} V={V} S={S} SG={SG} kernel={kern}", flush=True)
+                C = _spmm(g, B, pc.make_params(V=V, S=S, SG=SG), K, kernel=kern)
+                _check(C, ref, bound, f"{case} K={K} V={V} S={S} SG={SG} {kern}")
+
+
+@pytest.mark.parametrize("name", ["rmat20", "road"])
+@pytest.mark.parametrize("V,S,SG", [(1, 0, 0), (2, 0, 0), (1, 1, 0), (2, 1, 16)])
+def test_device_arrays_bit_exact(name, V, S, SG):
+    g = _graph(name)
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=S, SG=SG))
+    e = pc.pcsr_export(h)
+    r = pf.pcsr_ref(g.n_rows, g.rowptr, g.colidx, g.vals, V, S, SG, 64)
+    for k in ("P", "M", "nnz_v", "V", "SG"):
+        assert e[k] == r[k]
+    for k in ("rowptr", "colidx", "trow"):
+        assert np.array_equal(e[k], r[k]), k
+    assert np.array_equal(e["val"].view(np.uint32), r["val"].view(np.uint32))
+    h.close()
+
+
+def test_device_csr_input_and_side_stream():
+    g = _graph("sbm")
+    K = 64
+    B, ref, bound = _oracle("sbm", g, K, "uniform")
+    rp, ci, va = (torch.from_numpy(x).cuda() for x in (g.rowptr, g.colidx, g.vals))
+    h = pc.pcsr_build(g.n_rows, g.n_cols, rp, ci, va, pc.make_params(V=2, S=1, SG=16))
+    s = torch.cuda.Stream()
+    Bd = torch.from_numpy(B).cuda()
+    Cd = torch.empty((g.n_rows, K), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        pc.pcsr_spmm(h, Bd, Cd, K, s)
+    s.synchronize()
+    _check(Cd.cpu().numpy(), ref, bound, "device csr")
+    h.close()
+
+
+def test_unsplit_path_is_bit_reproducible_and_overwrites():
+    g = _graph("rmat20")
+    K = 32
+    B, ref, bound = _oracle("rmat20", g, K, "normal")
+    for V in (1, 2):
+        a = _spmm(g, B, pc.make_params(V=V, S=0), K, prefill=float("nan"))
+        b = _spmm(g, B, pc.make_params(V=V, S=0), K, prefill=123.0)
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    # balancing on: rows are cleared before accumulation, whatever C held
+    c = _spmm(g, B, pc.make_params(V=1, S=1, SG=8), K, prefill=1e30)
+    _check(c, ref, bound, "S=1 prefilled")
+
+
+def test_identity_and_all_ones_closed_forms():
+    n, K = 1000, 48
+    eye = synth.Graph("eye", n, n, np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32),
+                      np.ones(n, np.float32))
+    B = synth.dense_operand(n, K, "normal", 1)
+    for V in (1, 2):
+        C = _spmm(eye, B, pc.make_params(V=V), K)
+        assert np.array_equal(C.view(np.uint32), B.view(np.uint32))
+    g = _graph("sbm")
+    C = _spmm(g, np.ones((g.n_cols, 16), np.float32), pc.make_params(V=1, S=1, SG=8), 16)
+    assert np.allclose(C, 1.0, rtol=0, atol=2e-6)
+
+
+def test_long_row_accumulation_stays_in_tolerance():
+    """One row with 150k nonzeros and all-ones B: the worst case for fp32 error growth."""
+    n, L = 8, 150_000
+    rowptr = np.zeros(n + 1, np.int32)
+    rowptr[3:] = L
+    g = synth.Graph("long", n, L, rowptr, np.arange(L, dtype=np.int32),
+                    np.random.default_rng(0).uniform(0.5, 1.5, L).astype(np.float32))
+    B = np.ones((L, 16), np.float32)
+    ref, bound = oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+    for S in (0, 1):
+        for kern in (None, (64, 1, 1, 1), (4, 4, 1, 4)):
+            C = _spmm(g, B, pc.make_params(V=1, S=S, SG=64 if S else 0), 16, kernel=kern)
+            _check(C, ref, bound, f"long row S={S} {kern}")
+
+
+def test_full_size_road_sampled_rows():
+    """The bench workload at full size in the bench's launch configuration; the oracle
+    recomputes a sample of rows one by one."""
+    g = synth.workload("road", "full")
+    K = 128
+    B = synth.dense_operand(g.n_cols, K, "normal", 2)
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params())
+    Bd = torch.from_numpy(B).cuda()
+    Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+    pc.pcsr_spmm(h, Bd, Cd, K)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    deg = g.degrees()
+    rows = np.unique(np.concatenate([rng.integers(0, g.n_rows, 20000), [0, g.n_rows - 1],
+                                     np.argsort(deg)[-50:], np.nonzero(deg == 0)[0][:50]]))
+    ref, bound = oracle.spmm_rows(g.rowptr, g.colidx, g.vals, B, rows)
+    got = Cd[torch.from_numpy(rows).cuda()].cpu().numpy()
+    _check(got, ref, bound, "road full sampled")
+    # property that holds at any size: nothing left unwritten
+    assert not torch.isnan(Cd).any().item()
+    h.close()

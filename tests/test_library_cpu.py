@@ -1,0 +1,157 @@
+"""CPU-side checks of the C-ABI library: exported symbols, host PCSR generation bit-exact
+against the numpy format reference, feature extraction, error paths.  No GPU calls."""
+import ctypes
+import pathlib
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_15695_amd as pc
+from oracle import pcsr_format as pf
+from paper_2605_15695_amd import binding, synth
+from tests.helpers import random_csr
+
+ROOT = pathlib.Path(__file__).resolve().parent.parent
+HOST = pc.PCSR_FLAG_HOST_ONLY
+
+
+def _bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def _assert_same(e, r):
+    for k in ("P", "M", "nnz_v", "V", "SG"):
+        assert e[k] == r[k], k
+    for k in ("rowptr", "colidx", "val", "trow"):
+        assert e[k].dtype == r[k].dtype and np.array_equal(_bits(e[k]), _bits(r[k])), k
+
+
+def test_every_declared_symbol_is_exported():
+    header = (ROOT / "include" / "pcsr.h").read_text()
+    names = set(re.findall(r"^(?:int|int32_t|const char \*)\s*(pcsr_[a-z_]+)\(", header, re.M))
+    assert len(names) >= 11
+    assert {"pcsr_build", "pcsr_spmm", "pcsr_free"} <= names
+    lib = ctypes.CDLL(str(binding.LIB_PATH))
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+@pytest.mark.parametrize("name", ["poisson", "road", "rmat20", "sbm", "sbm_shuffled", "rmat22"])
+@pytest.mark.parametrize("V", [1, 2])
+@pytest.mark.parametrize("S,SG,omega", [(0, 0, 0), (1, 0, 0), (1, 0, 32), (1, 5, 0)])
+def test_host_generation_bit_exact(name, V, S, SG, omega):
+    g = synth.workload(name, "small")
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals,
+                      pc.make_params(V=V, S=S, SG=SG, omega=omega, flags=HOST))
+    _assert_same(pc.pcsr_export(h), pf.pcsr_ref(g.n_rows, g.rowptr, g.colidx, g.vals, V, S, SG, omega or 64))
+    h.close()
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 3, 17])
+@pytest.mark.parametrize("V", [1, 2])
+@pytest.mark.parametrize("S", [0, 1])
+def test_host_generation_tiny_and_degenerate(n, V, S):
+    rng = np.random.default_rng(n + 7)
+    if n == 0:
+        rowptr, colidx, vals = np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32)
+    else:
+        rowptr, colidx, vals, _ = random_csr(rng, n, n + 2, 0.4, empty_rows=(0,) if n > 1 else ())
+    h = pc.pcsr_build(n, n + 2, rowptr, colidx, vals, pc.make_params(V=V, S=S, SG=2 if S else 0, flags=HOST))
+    _assert_same(pc.pcsr_export(h), pf.pcsr_ref(n, rowptr, colidx, vals, V, S, 2 if S else 0, 64))
+
+
+def test_explicit_zero_is_kept_as_a_vector():
+    rowptr = np.array([0, 2, 3], np.int32)
+    colidx = np.array([1, 4, 2], np.int32)
+    vals = np.array([0.0, 3.0, -0.0], np.float32)
+    for V in (1, 2):
+        h = pc.pcsr_build(2, 5, rowptr, colidx, vals, pc.make_params(V=V, flags=HOST))
+        e = pc.pcsr_export(h)
+        _assert_same(e, pf.pcsr_ref(2, rowptr, colidx, vals, V, 0))
+        assert e["nnz_v"] == 3
+
+
+@pytest.mark.parametrize("name", ["poisson", "road", "rmat20", "sbm"])
+@pytest.mark.parametrize("omega", [32, 64])
+def test_features_match_reference(name, omega):
+    g = synth.workload(name, "small")
+    f = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega)
+    r = pf.features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega)
+    assert np.allclose(f, r, rtol=1e-12, atol=0)
+    assert f[14] == 0.0 and 0.0 <= f[15] <= 0.5 and f[9] >= 1.0 and f[10] >= 1.0
+
+
+def test_gap_export_matches_table2():
+    for line in (ROOT / "tests/golden/table2_gap.txt").read_text().splitlines():
+        if line.strip() and not line.startswith("#"):
+            dim, F, gap = map(int, line.split())
+            assert pc.pcsr_mac_job_gap(dim, F, 32) == gap
+    assert pc.pcsr_mac_job_gap(0, 1, 32) == -1
+
+
+def _expect(code, *args, **kw):
+    with pytest.raises(pc.PcsrError) as ei:
+        pc.pcsr_build(*args, **kw)
+    assert ei.value.code == code
+
+
+def test_error_paths():
+    rp = np.array([0, 2, 3], np.int32)
+    ci = np.array([0, 1, 2], np.int32)
+    va = np.ones(3, np.float32)
+    P = lambda **k: pc.make_params(flags=HOST, **k)  # noqa: E731
+    _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(V=3))
+    _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(S=2))
+    _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(lanes_per_row=3))
+    _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(vec=3))
+    _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(waves_per_wg=16))
+    _expect(binding.PCSR_E_INVALID_ARG, 2, 3, rp, ci, va, P(SG=-1))
+    # malformed CSR
+    _expect(binding.PCSR_E_BAD_CSR, 2, 3, np.array([0, 3, 2], np.int32), ci, va, P())        # not monotone
+    _expect(binding.PCSR_E_BAD_CSR, 2, 3, np.array([1, 2, 3], np.int32), ci, va, P())        # start != 0
+    _expect(binding.PCSR_E_BAD_CSR, 2, 3, np.array([0, 2, 2], np.int32), ci, va, P())        # end != nnz
+    _expect(binding.PCSR_E_BAD_CSR, 2, 3, rp, np.array([0, 3, 2], np.int32), va, P())        # col >= n_cols
+    _expect(binding.PCSR_E_BAD_CSR, 2, 3, rp, np.array([0, -1, 2], np.int32), va, P())       # negative col
+    _expect(binding.PCSR_E_BAD_CSR, 2, 3, rp, np.array([1, 0, 2], np.int32), va, P())        # unsorted
+    _expect(binding.PCSR_E_BAD_CSR, 2, 3, rp, np.array([1, 1, 2], np.int32), va, P())        # duplicate
+    # reserved must be zero
+    p = P()
+    p.reserved[1] = 5
+    _expect(binding.PCSR_E_INVALID_ARG, 2, 3, rp, ci, va, p)
+    # SpMM on a host-only handle is refused, never silently computed elsewhere
+    h = pc.pcsr_build(2, 3, rp, ci, va, P())
+    lib = binding._lib()
+    assert lib.pcsr_spmm(h.raw, None, None, 4, None) == binding.PCSR_E_UNSUPPORTED
+    assert lib.pcsr_spmm(None, None, None, 4, None) == binding.PCSR_E_INVALID_ARG
+    assert lib.pcsr_free(None) == 0
+    assert "CSR" in pc.pcsr_strerror(binding.PCSR_E_BAD_CSR)
+
+
+def test_launch_resolution():
+    g = synth.workload("poisson", "small")
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(flags=HOST))
+    q = pc.pcsr_query_launch(h, 16)
+    assert (q["lanes_per_row"], q["vec"], q["rep"]) == (4, 4, 1) and q["grid_y"] == 1
+    assert q["grid_x"] == -(-g.n_rows // (q["waves_per_wg"] * 16))
+    q = pc.pcsr_query_launch(h, 512)
+    assert q["lanes_per_row"] * q["vec"] * q["rep"] * q["grid_y"] >= 512
+    q = pc.pcsr_query_launch(h, 33)
+    assert q["vec"] == 1 and q["lanes_per_row"] * q["rep"] * q["grid_y"] >= 33
+    pc.pcsr_set_kernel_params(h, 8, 2, 2, 1)
+    q = pc.pcsr_query_launch(h, 128)
+    assert (q["lanes_per_row"], q["vec"], q["rep"], q["waves_per_wg"], q["grid_y"]) == (8, 2, 2, 1, 4)
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_query_launch(h, 33)          # vec = 2 does not divide 33
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_set_kernel_params(h, 5, 0, 0, 0)
+
+
+def test_select_returns_valid_tuple():
+    for name in ("road", "rmat20", "sbm"):
+        g = synth.workload(name, "small")
+        f = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
+        p = pc.pcsr_select(f, 64)
+        assert p.V in (1, 2) and p.S in (0, 1)
+    assert pc.pcsr_select(pc.pcsr_features(*(lambda g: (g.n_rows, g.n_cols, g.rowptr, g.colidx))(
+        synth.workload("road", "small"))), 64).S == 0
