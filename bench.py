@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--no-xcd-remap", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB elementwise copy kernel (reads 1 GiB, writes 1 GiB) so a "
+                         "rocprofv3 --pmc run of this command holds a dispatch of known traffic")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (no sharded path exists)",
@@ -107,6 +110,14 @@ def main() -> int:
     per_launch_ms = [a.elapsed_time(b) for a, b in evs]
     ms_per_step = wall * 1e3 / args.steps
     kern_ms = statistics.fmean(per_launch_ms)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     flops = 2.0 * g.nnz * K
     bytes_min = algorithmic_bytes(g, K)

@@ -9,6 +9,7 @@ PKG = pathlib.Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libpcsr.so"
+BASELINE_LIB = PKG / "libpcsr_baseline.so"
 
 HIPCC = "/opt/rocm/bin/hipcc"
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument"]
@@ -35,8 +36,12 @@ def build(verbose: bool = False) -> pathlib.Path:
     cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", *map(str, objs), "-o", str(LIB),
            "-lpthread"]
     subprocess.run(cmd, check=True)
+    # vendor baseline used by the benchmarks (links hipSPARSE; not part of libpcsr.so)
+    base = _compile("baseline_hipsparse.cpp")
+    subprocess.run([HIPCC, "-shared", "-fPIC", str(base), "-o", str(BASELINE_LIB),
+                    "-L/opt/rocm/lib", "-lhipsparse", "-Wl,-rpath,/opt/rocm/lib"], check=True)
     if verbose:
-        print(LIB)
+        print(LIB, BASELINE_LIB)
     return LIB
 
 

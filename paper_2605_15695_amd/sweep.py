@@ -1,0 +1,227 @@
+"""Exhaustive configuration sweep on one MI355X: every PCSR format tuple (V, S, SG) times
+every kernel launch shape (lanes_per_row, vec, rep, waves_per_wg, XCD remap) for one
+workload and width K, timed with device events, beside hipSPARSE SpMM on the same
+arrays.  One JSON line per timing goes to --out; the recorded sweeps are the data the
+library's selection rule (pcsr_select) is distilled from, in the role the paper gives
+the training set of its SpMM-decider (Section 5.2).
+
+Outputs of all tuples are compared on the GPU with the first tuple's output (max
+|difference| relative to max |C|) as a consistency diagnostic; parity against the
+CPU oracle is the job of the tests and of bench.py.
+
+    python -m paper_2605_15695_amd.sweep --workload rmat20 --K 64 --out gpurun_out/sweep_rmat20.jsonl
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import itertools
+import json
+import pathlib
+import statistics
+import sys
+import time
+
+import numpy as np
+
+from . import binding as pc
+from . import synth
+
+HBM_PEAK_GBS = 8000.0
+HIPSPARSE_ALGS = {"default": 0, "csr_alg1": 4, "csr_alg2": 6, "csr_alg3": 12}
+
+
+def algorithmic_bytes(g, K: int) -> int:
+    n_refcols = int(np.unique(g.colidx).shape[0])
+    return g.nnz * 8 + (g.n_rows + 1) * 4 + n_refcols * K * 4 + g.n_rows * K * 4
+
+
+def kernel_shapes(K: int, quick: bool):
+    """(lanes_per_row, vec, rep) with a tile of lanes*vec*rep columns that covers K in one
+    or two grid.y slices without a fully idle repeat."""
+    shapes = []
+    for vec in (4, 2, 1):
+        if K % vec:
+            continue
+        if quick and vec != (4 if K % 4 == 0 else (2 if K % 2 == 0 else 1)):
+            continue
+        for lpr in (4, 8, 16, 32, 64):
+            for rep in (1, 2, 4):
+                tile = lpr * vec * rep
+                if tile * 2 < K:
+                    continue                      # more than two slices: A re-read too often
+                if lpr * vec * (rep - 1) >= K:
+                    continue                      # a whole repeat would be idle
+                if lpr * vec >= 2 * K and lpr > 4:
+                    continue                      # half of the lanes idle
+                shapes.append((lpr, vec, rep))
+    return shapes
+
+
+def time_launches(fn, stream, torch, warmup: int, reps: int):
+    for _ in range(warmup):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(reps)]
+    torch.cuda.synchronize()
+    for a, b in evs:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    torch.cuda.synchronize()
+    ts = [a.elapsed_time(b) for a, b in evs]
+    return statistics.median(ts), min(ts)
+
+
+def _baseline_lib():
+    path = pathlib.Path(__file__).resolve().parent / "libpcsr_baseline.so"
+    lib = ctypes.CDLL(str(path))
+    i64, i32, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+    lib.hsp_spmm_create.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, i32, i32, vp, ctypes.POINTER(vp)]
+    lib.hsp_spmm_run.argtypes = [vp]
+    lib.hsp_spmm_destroy.argtypes = [vp]
+    lib.hsp_spmm_buffer_bytes.argtypes = [vp]
+    lib.hsp_spmm_buffer_bytes.restype = i64
+    return lib
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", required=True)
+    ap.add_argument("--size", default="full")
+    ap.add_argument("--K", type=int, nargs="*", default=None)
+    ap.add_argument("--out", required=True)
+    ap.add_argument("--quick", action="store_true", help="widest vector only, waves in {2,4}")
+    ap.add_argument("--reps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--formats", default="all", help="all | comma list of V:S:SG, e.g. 1:0:0,1:1:64")
+    ap.add_argument("--no-hipsparse", action="store_true")
+    args = ap.parse_args(argv)
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("sweep: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    out = open(args.out, "a")
+
+    def emit(rec):
+        out.write(json.dumps(rec) + "\n")
+        out.flush()
+
+    t0 = time.time()
+    g = synth.workload(args.workload, args.size)
+    spec = synth.WORKLOADS[args.workload]
+    Ks = args.K or spec["K"]
+    feats = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
+    print(f"[sweep] {args.workload}-{args.size}: n={g.n_rows} nnz={g.nnz} generated in {time.time()-t0:.1f}s",
+          flush=True)
+    emit({"kind": "graph", "workload": args.workload, "size": args.size, "n": g.n_rows, "nnz": g.nnz,
+          "features": dict(zip(pc.FEATURE_NAMES, map(float, feats)))})
+
+    if args.formats == "all":
+        sg_eq3 = 0
+        formats = [(1, 0, 0), (2, 0, 0), (1, 1, sg_eq3), (2, 1, sg_eq3), (1, 1, 256), (1, 1, 1024)]
+    else:
+        formats = [tuple(int(x) for x in f.split(":")) for f in args.formats.split(",")]
+
+    d_rowptr = torch.from_numpy(g.rowptr).cuda()
+    d_colidx = torch.from_numpy(g.colidx).cuda()
+    d_vals = torch.from_numpy(g.vals).cuda()
+
+    handles = {}
+    for fmt in formats:
+        V, S, SG = fmt
+        t0 = time.time()
+        handles[fmt] = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals,
+                                     pc.make_params(V=V, S=S, SG=SG, flags=pc.PCSR_FLAG_NO_VALIDATE))
+        print(f"[sweep] built V={V} S={S} SG={SG} in {time.time()-t0:.2f}s", flush=True)
+
+    for K in Ks:
+        B = synth.dense_operand(g.n_cols, K, spec["B"], 2)
+        Bd = torch.from_numpy(B).cuda()
+        del B
+        Cd = torch.empty((g.n_rows, K), dtype=torch.float32, device="cuda")
+        Cref = None
+        flops = 2.0 * g.nnz * K
+        bytes_min = algorithmic_bytes(g, K)
+        base = {"workload": args.workload, "size": args.size, "K": K, "nnz": g.nnz, "n": g.n_rows,
+                "bytes_min": bytes_min}
+        best = (float("inf"), None)
+        for fmt in formats:
+            V, S, SG = fmt
+            h = handles[fmt]
+            waves_list = (2, 4) if args.quick else (1, 2, 4, 8)
+            for (lpr, vec, rep), waves, remap in itertools.product(kernel_shapes(K, args.quick), waves_list,
+                                                                   (1, 0)):
+                if args.quick and not remap:
+                    continue
+                pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, 0 if remap else pc.PCSR_FLAG_NO_XCD_REMAP)
+                try:
+                    q = pc.pcsr_query_launch(h, K)
+                except pc.PcsrError:
+                    continue
+                Cd.fill_(float("nan"))
+                med, mn = time_launches(lambda: pc.pcsr_spmm(h, Bd, Cd, K, stream), stream, torch,
+                                        args.warmup, args.reps)
+                if Cref is None:
+                    Cref = Cd.clone()
+                    scale = float(Cref.abs().max().item()) or 1.0
+                    dev = 0.0
+                else:
+                    dev = float((Cd - Cref).abs().max().item()) / scale
+                rec = dict(base, kind="pcsr", V=V, S=S, SG=SG, lanes_per_row=lpr, vec=vec, rep=rep,
+                           waves_per_wg=waves, xcd_remap=remap, grid_x=q["grid_x"], grid_y=q["grid_y"],
+                           ms_median=med, ms_min=mn, gflops=flops / med / 1e6,
+                           roofline_frac=bytes_min / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, max_rel_dev=dev)
+                emit(rec)
+                if med < best[0]:
+                    best = (med, rec)
+            print(f"[sweep] K={K} V={V} S={S} SG={SG} done; best so far {best[0]:.4f} ms", flush=True)
+
+        hs_best = (float("inf"), None)
+        if not args.no_hipsparse:
+            lib = _baseline_lib()
+            for name, alg in HIPSPARSE_ALGS.items():
+                ctx = ctypes.c_void_p()
+                t0 = time.time()
+                rc = lib.hsp_spmm_create(g.n_rows, g.n_cols, g.nnz, d_rowptr.data_ptr(), d_colidx.data_ptr(),
+                                         d_vals.data_ptr(), Bd.data_ptr(), Cd.data_ptr(), K, alg,
+                                         stream.cuda_stream, ctypes.byref(ctx))
+                torch.cuda.synchronize()
+                prep = time.time() - t0
+                if rc != 0:
+                    emit(dict(base, kind="hipsparse", alg=name, error=rc))
+                    continue
+                Cd.fill_(float("nan"))
+                med, mn = time_launches(lambda: lib.hsp_spmm_run(ctx), stream, torch, args.warmup, args.reps)
+                dev = float((Cd - Cref).abs().max().item()) / scale if Cref is not None else None
+                rec = dict(base, kind="hipsparse", alg=name, ms_median=med, ms_min=mn,
+                           gflops=flops / med / 1e6, preprocess_s=prep,
+                           buffer_bytes=int(lib.hsp_spmm_buffer_bytes(ctx)),
+                           roofline_frac=bytes_min / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, max_rel_dev=dev)
+                emit(rec)
+                lib.hsp_spmm_destroy(ctx)
+                if med < hs_best[0]:
+                    hs_best = (med, rec)
+                print(f"[sweep] K={K} hipsparse {name}: {med:.4f} ms", flush=True)
+        summary = dict(base, kind="summary", pcsr_best=best[1], hipsparse_best=hs_best[1],
+                       speedup_vs_hipsparse=(hs_best[0] / best[0]) if hs_best[1] and best[1] else None)
+        emit(summary)
+        b = best[1]
+        print(f"[sweep] K={K} BEST {b['ms_median']:.4f} ms {b['gflops']:.0f} GFLOP/s roofline {b['roofline_frac']:.3f} "
+              f"V={b['V']} S={b['S']} SG={b['SG']} lpr={b['lanes_per_row']} vec={b['vec']} rep={b['rep']} "
+              f"waves={b['waves_per_wg']} remap={b['xcd_remap']} | hipsparse best "
+              f"{hs_best[0]:.4f} ms ({hs_best[1]['alg'] if hs_best[1] else '-'})", flush=True)
+        del Bd, Cd, Cref
+        torch.cuda.empty_cache()
+    for h in handles.values():
+        h.close()
+    out.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
