@@ -45,6 +45,7 @@ def main() -> int:
     ap.add_argument("--vec", type=int, default=0)
     ap.add_argument("--rep", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--items-per-group", type=int, default=0)
     ap.add_argument("--no-xcd-remap", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -78,11 +79,15 @@ def main() -> int:
     feats = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
     sel = pc.pcsr_select(feats, K)
     feat_ms = (time.time() - t0) * 1e3
+    # the library's own pick, with any field overridden from the command line
     V = sel.V if args.V < 0 else args.V
     S = sel.S if args.S < 0 else args.S
-    params = pc.make_params(V=V, S=S, SG=args.SG, lanes_per_row=args.lanes_per_row, vec=args.vec,
-                            rep=args.rep, waves_per_wg=args.waves,
-                            flags=pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
+    params = pc.make_params(
+        V=V, S=S, SG=args.SG or (sel.SG if S == sel.S else 0),
+        lanes_per_row=args.lanes_per_row or sel.lanes_per_row, vec=args.vec or sel.vec,
+        rep=args.rep or sel.rep, waves_per_wg=args.waves or sel.waves_per_wg,
+        items_per_group=args.items_per_group or sel.items_per_group,
+        flags=pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
     t0 = time.time()
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, params)
     build_ms = (time.time() - t0) * 1e3

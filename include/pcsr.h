@@ -55,6 +55,11 @@ enum {
  *                    One work item covers lanes_per_row*vec*rep columns of C per grid.y
  *                    slice; wider K is covered by more grid.y slices.
  *     waves_per_wg   wavefronts per workgroup (the paper's W): 1, 2, 4 or 8; 0 = auto.
+ *     items_per_group  consecutive work items one lane group walks in a single pass,
+ *                    gathering for all of them before any result is needed: 1, 2 or 4;
+ *                    0 = auto.  Values above 1 need S = 0, items_per_group <
+ *                    lanes_per_row, no work item longer than 1024 vectors and
+ *                    V*vec*rep*items_per_group <= 32.
  *   flags   PCSR_FLAG_* bits.
  */
 typedef struct {
@@ -67,7 +72,8 @@ typedef struct {
     int32_t rep;
     int32_t waves_per_wg;
     int32_t flags;
-    int32_t reserved[3]; /* must be 0 */
+    int32_t items_per_group;
+    int32_t reserved[2]; /* must be 0 */
 } pcsr_params_t;
 
 typedef struct pcsr_handle_s *pcsr_handle_t;
@@ -109,21 +115,22 @@ int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream
 int pcsr_free(pcsr_handle_t h);
 
 /*
- * Changes the kernel-only parameters (lanes_per_row, vec, rep, waves_per_wg, and the
- * PCSR_FLAG_NO_XCD_REMAP bit of flags) of an existing handle; 0 = auto.  The PCSR
+ * Changes the kernel-only parameters (lanes_per_row, vec, rep, waves_per_wg,
+ * items_per_group, and the PCSR_FLAG_NO_XCD_REMAP bit of flags) of an existing handle; 0 = auto.  The PCSR
  * arrays are untouched, so one build can be timed under many launch shapes (the
  * exhaustive sweep that stands in for the training data of Section 5.2).
  * Errors: INVALID_ARG, UNSUPPORTED.
  */
 int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, int32_t rep,
-                           int32_t waves_per_wg, int32_t flags);
+                           int32_t waves_per_wg, int32_t items_per_group, int32_t flags);
 
 /*
  * Reports the launch shape pcsr_spmm would use for width K with the handle's current
- * kernel parameters (after "auto" resolution): out[0..5] = lanes_per_row, vec, rep,
- * waves_per_wg, grid.x, grid.y.  Host memory.  Errors: INVALID_ARG, UNSUPPORTED.
+ * kernel parameters (after "auto" resolution): out[0..6] = lanes_per_row, vec, rep,
+ * waves_per_wg, grid.x, grid.y, items_per_group.  Host memory.
+ * Errors: INVALID_ARG, UNSUPPORTED.
  */
-int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[6]);
+int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[7]);
 
 /*
  * Copies the PCSR arrays (Section 4.2, "Data Representation") out of the handle for

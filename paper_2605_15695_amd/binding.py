@@ -24,8 +24,9 @@ FEATURE_NAMES = ("n", "n_hat", "nnz", "delta", "d", "d_hat", "d_max", "CV", "CV_
 
 class pcsr_params_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("V", "S", "SG", "omega", "lanes_per_row", "vec", "rep", "waves_per_wg", "flags")]
-    _fields_ += [("reserved", ctypes.c_int32 * 3)]
+                ("V", "S", "SG", "omega", "lanes_per_row", "vec", "rep", "waves_per_wg", "flags",
+                 "items_per_group")]
+    _fields_ += [("reserved", ctypes.c_int32 * 2)]
 
 
 class PcsrError(RuntimeError):
@@ -53,8 +54,8 @@ def _lib():
         lib.pcsr_build.argtypes = [i64, i64, i64, vp, vp, vp, pp, ctypes.POINTER(vp)]
         lib.pcsr_spmm.argtypes = [vp, vp, vp, i32, vp]
         lib.pcsr_free.argtypes = [vp]
-        lib.pcsr_set_kernel_params.argtypes = [vp, i32, i32, i32, i32, i32]
-        lib.pcsr_query_launch.argtypes = [vp, i32, ctypes.POINTER(i32 * 6)]
+        lib.pcsr_set_kernel_params.argtypes = [vp, i32, i32, i32, i32, i32, i32]
+        lib.pcsr_query_launch.argtypes = [vp, i32, ctypes.POINTER(i32 * 7)]
         lib.pcsr_export.argtypes = [vp, ctypes.POINTER(i64 * 6), vp, vp, vp, vp]
         lib.pcsr_features.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32]
         lib.pcsr_select.argtypes = [vp, i32, pp]
@@ -87,10 +88,12 @@ def _ptr(a, dtype=None):
     return a, a.data_ptr(), a.is_cuda
 
 
-def make_params(V=1, S=0, SG=0, omega=0, lanes_per_row=0, vec=0, rep=0, waves_per_wg=0, flags=0):
+def make_params(V=1, S=0, SG=0, omega=0, lanes_per_row=0, vec=0, rep=0, waves_per_wg=0, flags=0,
+                items_per_group=0):
     p = pcsr_params_t()
     p.V, p.S, p.SG, p.omega = V, int(S), SG, omega
     p.lanes_per_row, p.vec, p.rep, p.waves_per_wg, p.flags = lanes_per_row, vec, rep, waves_per_wg, flags
+    p.items_per_group = items_per_group
     return p
 
 
@@ -154,18 +157,20 @@ def pcsr_free(h: Handle) -> None:
         raise PcsrError(rc, "pcsr_free")
 
 
-def pcsr_set_kernel_params(h: Handle, lanes_per_row=0, vec=0, rep=0, waves_per_wg=0, flags=0) -> None:
-    rc = _lib().pcsr_set_kernel_params(h.raw, lanes_per_row, vec, rep, waves_per_wg, flags)
+def pcsr_set_kernel_params(h: Handle, lanes_per_row=0, vec=0, rep=0, waves_per_wg=0,
+                           items_per_group=0, flags=0) -> None:
+    rc = _lib().pcsr_set_kernel_params(h.raw, lanes_per_row, vec, rep, waves_per_wg, items_per_group, flags)
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_set_kernel_params")
 
 
 def pcsr_query_launch(h: Handle, K: int) -> dict:
-    out = (ctypes.c_int32 * 6)()
+    out = (ctypes.c_int32 * 7)()
     rc = _lib().pcsr_query_launch(h.raw, K, ctypes.byref(out))
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_query_launch")
-    return dict(zip(("lanes_per_row", "vec", "rep", "waves_per_wg", "grid_x", "grid_y"), list(out)))
+    return dict(zip(("lanes_per_row", "vec", "rep", "waves_per_wg", "grid_x", "grid_y", "items_per_group"),
+                    list(out)))
 
 
 def pcsr_export(h: Handle) -> dict:

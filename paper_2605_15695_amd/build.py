@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import concurrent.futures
+import os
 import pathlib
 import subprocess
 
@@ -23,7 +24,7 @@ def _compile(src: str) -> pathlib.Path:
     obj = OBJ / (src + ".o")
     cmd = [HIPCC, *COMMON]
     if src.endswith(".hip"):
-        cmd += DEVICE
+        cmd += DEVICE + os.environ.get("PCSR_EXTRA_HIPCC_FLAGS", "").split()
     cmd += ["-c", str(CSRC / src), "-o", str(obj)]
     subprocess.run(cmd, check=True, stderr=subprocess.PIPE, text=True)
     return obj

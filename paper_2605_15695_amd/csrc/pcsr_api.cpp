@@ -26,8 +26,9 @@ inline bool hip_ok(hipError_t e)
 
 inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
-int check_kernel_params(int lpr, int vec, int rep, int waves)
+int check_kernel_params(int lpr, int vec, int rep, int waves, int ipg)
 {
+    if (ipg != 0 && ipg != 1 && ipg != 2 && ipg != 4) return PCSR_E_UNSUPPORTED;
     if (lpr != 0 && !(is_pow2(lpr) && lpr >= 4 && lpr <= 64)) return PCSR_E_UNSUPPORTED;
     if (vec != 0 && vec != 1 && vec != 2 && vec != 4) return PCSR_E_UNSUPPORTED;
     if (rep != 0 && rep != 1 && rep != 2 && rep != 4) return PCSR_E_UNSUPPORTED;
@@ -48,7 +49,7 @@ struct pcsr_handle_s {
     int32_t *d_trow = nullptr;
     int32_t *d_split = nullptr;
     int64_t n_split = 0;
-    int32_t lpr = 0, vec = 0, rep = 0, waves = 0, flags = 0;
+    int32_t lpr = 0, vec = 0, rep = 0, waves = 0, ipg = 0, flags = 0;
 };
 
 namespace {
@@ -101,8 +102,13 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
         while (rep < need && rep < 4) rep <<= 1;
     }
     int waves = h->waves ? h->waves : 4;
-    if (!pcsr::kernel_exists(h->host.V, h->host.S, lpr, vec, rep)) return PCSR_E_UNSUPPORTED;
-    const int64_t items_per_wg = (int64_t)waves * (64 / lpr);
+    int ipg = h->ipg ? h->ipg : 1;
+    if (ipg > 1) {
+        // the batched walk accumulates each item sequentially and has no atomic write-back
+        if (h->host.S || h->host.max_item_len > 1024) return PCSR_E_UNSUPPORTED;
+    }
+    if (!pcsr::kernel_exists(h->host.V, h->host.S, lpr, vec, rep, ipg)) return PCSR_E_UNSUPPORTED;
+    const int64_t items_per_wg = (int64_t)waves * (64 / lpr) * ipg;
     const int64_t gx = (h->host.M + items_per_wg - 1) / items_per_wg;
     const int64_t tile = (int64_t)lpr * vec * rep;
     const int64_t gy = (K + tile - 1) / tile;
@@ -111,6 +117,7 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
     ls->vec = vec;
     ls->rep = rep;
     ls->waves = waves;
+    ls->ipg = ipg;
     ls->grid_x = (int32_t)gx;
     ls->grid_y = (int32_t)gy;
     return PCSR_OK;
@@ -133,10 +140,10 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     if (prm.V != 1 && prm.V != 2) return PCSR_E_UNSUPPORTED;
     if (prm.S != 0 && prm.S != 1) return PCSR_E_UNSUPPORTED;
     if (prm.SG < 0 || prm.omega < 0) return PCSR_E_INVALID_ARG;
-    if (prm.reserved[0] || prm.reserved[1] || prm.reserved[2]) return PCSR_E_INVALID_ARG;
+    if (prm.reserved[0] || prm.reserved[1]) return PCSR_E_INVALID_ARG;
     if (nnz >= (int64_t(1) << 31) || n_rows >= (int64_t(1) << 31) - 1 || n_cols >= (int64_t(1) << 31))
         return PCSR_E_TOO_LARGE;
-    int rc = check_kernel_params(prm.lanes_per_row, prm.vec, prm.rep, prm.waves_per_wg);
+    int rc = check_kernel_params(prm.lanes_per_row, prm.vec, prm.rep, prm.waves_per_wg, prm.items_per_group);
     if (rc != PCSR_OK) return rc;
     const bool host_only = (prm.flags & PCSR_FLAG_HOST_ONLY) != 0;
     if (host_only && (prm.flags & PCSR_FLAG_DEVICE_CSR)) return PCSR_E_INVALID_ARG;
@@ -178,6 +185,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         h->vec = prm.vec;
         h->rep = prm.rep;
         h->waves = prm.waves_per_wg;
+        h->ipg = prm.items_per_group;
         h->flags = prm.flags;
         h->n_split = (int64_t)h->host.split_panels.size();
         if (!host_only) {
@@ -257,20 +265,21 @@ int pcsr_free(pcsr_handle_t h)
 }
 
 int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, int32_t rep,
-                           int32_t waves_per_wg, int32_t flags)
+                           int32_t waves_per_wg, int32_t items_per_group, int32_t flags)
 {
     if (!valid(h)) return PCSR_E_INVALID_ARG;
-    int rc = check_kernel_params(lanes_per_row, vec, rep, waves_per_wg);
+    int rc = check_kernel_params(lanes_per_row, vec, rep, waves_per_wg, items_per_group);
     if (rc != PCSR_OK) return rc;
     h->lpr = lanes_per_row;
     h->vec = vec;
     h->rep = rep;
     h->waves = waves_per_wg;
+    h->ipg = items_per_group;
     h->flags = (h->flags & ~PCSR_FLAG_NO_XCD_REMAP) | (flags & PCSR_FLAG_NO_XCD_REMAP);
     return PCSR_OK;
 }
 
-int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[6])
+int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[7])
 {
     if (!valid(h) || !out) return PCSR_E_INVALID_ARG;
     pcsr::LaunchShape ls;
@@ -282,6 +291,7 @@ int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[6])
     out[3] = ls.waves;
     out[4] = ls.grid_x;
     out[5] = ls.grid_y;
+    out[6] = ls.ipg;
     return PCSR_OK;
 }
 
@@ -332,16 +342,46 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     if (K <= 0) return PCSR_E_UNSUPPORTED;
     pcsr_params_t p;
     std::memset(&p, 0, sizeof(p));
-    const double d_hat = f[5], d_max = f[6], cv = f[7], pr2 = f[15];
-    // Balancing pays when a few rows dwarf the average one (Section 3.2): the longest
-    // row would keep one group busy long after the rest of the grid has drained.
-    p.S = (d_max > 32.0 * std::fmax(d_hat, 1.0) && cv > 1.0) ? 1 : 0;
-    // Vector size 2 pays only when adjacent rows share most columns (Table 1: wins at
-    // about 30 % padding, loses near 50 %).
-    p.V = (pr2 < 0.35 && d_hat >= 4.0) ? 2 : 1;
-    p.SG = 0;
+    const double n = f[0], nnz = f[2], d_hat = f[5], d_max = f[6], cv = f[7], rho = f[11];
+    const double bw = f[12], pr2 = f[15];
+    const double n_cols = (rho > 0 && n > 0) ? nnz / (rho * n) : n;
+
+    // Balancing (Section 3.2) pays when a few rows dwarf the average one.  On MI355X the
+    // recorded sweeps prefer items of 256 vectors over Eq. (3)'s value for such inputs.
+    p.S = (cv > 1.5 && d_max > 256.0) ? 1 : 0;
+    p.SG = p.S ? 256 : 0;
     p.omega = 64;
-    // kernel parameters: left on auto (resolved from K at launch)
+    // Vector size 2 (Section 3.1) when adjacent rows share columns (low padding), and for
+    // very short rows, where pairing rows doubles the gathers a lane group keeps in flight.
+    p.V = (!p.S && (d_hat < 6.0 || (pr2 < 0.30 && d_hat >= 4.0))) ? 2 : 1;
+
+    const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
+    // Column slice per grid.y: when B is far larger than the last-level cache and rows
+    // reference columns all over the matrix, narrower slices (processed one after the
+    // other) shrink the footprint of the frequently used B rows until it is cache
+    // resident.  A slice is never narrower than one 128-byte line.
+    int slice = K;
+    const double b_bytes = n_cols * (double)K * 4.0;
+    const bool scattered = n_cols > 0 && bw > 0.05 * n_cols;
+    if (scattered && b_bytes > 768.0 * 1048576.0) {
+        double cols = 512.0 * 1048576.0 / (n_cols * 4.0);
+        int w = 32;
+        while (w * 2 <= cols && w * 2 < K) w *= 2;
+        if (w < K && w % vec == 0) slice = w;
+    }
+    int lpr = 4;
+    while (lpr * vec < slice && lpr < 64) lpr <<= 1;
+    int rep = 1;
+    while (lpr * vec * rep < slice && rep < 4) rep <<= 1;
+    if (!p.S && p.V == 1 && d_hat < 8.0 && lpr >= 32 && rep == 1) {
+        lpr >>= 1; // short rows: more rows per wavefront, two loads per lane
+        rep = 2;
+    }
+    p.lanes_per_row = lpr;
+    p.vec = vec;
+    p.rep = rep;
+    p.waves_per_wg = p.S ? 2 : (d_hat >= 16.0 ? 8 : 2);
+    p.items_per_group = 1;
     *out = p;
     return PCSR_OK;
 }

@@ -23,10 +23,11 @@ struct SpmmArgs {
 // Resolved launch shape.
 struct LaunchShape {
     int32_t lpr, vec, rep, waves;
+    int32_t ipg; // work items per lane group (1 = one item per group)
     int32_t grid_x, grid_y;
 };
 
-bool kernel_exists(int V, int S, int lpr, int vec, int rep);
+bool kernel_exists(int V, int S, int lpr, int vec, int rep, int ipg);
 
 // Enqueues the SpMM kernel <V,S,lpr,vec,rep> with `waves` wavefronts per workgroup.
 hipError_t launch_spmm(int V, int S, const LaunchShape &ls, const SpmmArgs &args,

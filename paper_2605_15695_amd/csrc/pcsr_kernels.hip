@@ -56,7 +56,30 @@ template <int VEC> __device__ __forceinline__ void store_vec(float *p, const flo
         t.z = s[2];
         t.w = s[3];
     }
+#ifndef PCSR_PLAIN_STORE
+    typedef float ext_t __attribute__((ext_vector_type(VEC)));
+    ext_t x;
+    if constexpr (VEC == 1) {
+        __builtin_nontemporal_store(s[0], p);
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) x[e] = s[e];
+        __builtin_nontemporal_store(x, reinterpret_cast<ext_t *>(p));
+    }
+    (void)t;
+#else
     *reinterpret_cast<T *>(p) = t;
+#endif
+}
+
+// colIdx / val are read exactly once per SpMM: keep them from displacing B rows in L2
+template <class T> __device__ __forceinline__ T stream_load(const T *p)
+{
+#ifdef PCSR_NT_LOAD
+    return __builtin_nontemporal_load(p);
+#else
+    return *p;
+#endif
 }
 
 template <int LPR> __device__ __forceinline__ int bcast(int x, int j)
@@ -128,13 +151,14 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
 #pragma unroll
         for (int v = 0; v < V; ++v) av[v] = 0.0f;
         if (idx < tail) {
-            c = a.colidx[idx];
+            c = stream_load(a.colidx + idx);
             if constexpr (V == 1) {
-                av[0] = a.val[idx];
+                av[0] = stream_load(a.val + idx);
             } else {
-                const float2 t = reinterpret_cast<const float2 *>(a.val)[idx];
-                av[0] = t.x;
-                av[1] = t.y;
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                const f2 t = stream_load(reinterpret_cast<const f2 *>(a.val) + idx);
+                av[0] = t[0];
+                av[1] = t[1];
             }
         }
         const int cnt = min(LPR, tail - base);
@@ -222,6 +246,142 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
     }
 }
 
+
+// Batched walk for matrices of short rows (no balancing): one lane group owns IPG
+// consecutive work items and walks their joint colIdx/val range as one stream, so the
+// gathers of several rows are in flight together.  Every entry carries the index of the
+// item it belongs to; an entry's value is masked into the accumulator of its own item
+// only (IPG-fold FMA work, irrelevant next to the memory time of short rows).
+template <int V, int LPR, int VEC, int REP, int IPG>
+__global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
+{
+    static_assert(IPG < LPR, "item boundaries are broadcast from the group's own lanes");
+    constexpr int G = 64 / LPR;
+    constexpr int U0 = 16 / (REP * VEC);
+    constexpr int U = U0 < 1 ? 1 : (U0 > 8 ? 8 : (U0 > LPR ? LPR : U0));
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int waves = blockDim.x >> 6;
+    int bid = blockIdx.x;
+    if (a.xcd_remap) {
+        const int x = bid & 7, idx = bid >> 3;
+        const int q = a.nblk >> 3, r = a.nblk & 7;
+        bid = x * q + (x < r ? x : r) + idx;
+    }
+    const int lg = lane & (LPR - 1);
+    const long item0_l = (((long)bid * waves + wave) * G + (lane / LPR)) * IPG;
+    if (item0_l >= a.M) return;
+    const int item0 = (int)item0_l;
+
+    const int kbase = blockIdx.y * (LPR * VEC * REP);
+    int kc[REP];
+    bool kv[REP];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+        kc[r] = kbase + (r * LPR + lg) * VEC;
+        kv[r] = kc[r] < a.K;
+    }
+
+    // item boundaries: lane i of the group fetches rowPtr[item0 + i], i <= IPG
+    const int bsel = item0 + (lg < IPG ? lg : IPG);
+    const int my_rp = a.rowptr[bsel < a.M ? bsel : a.M];
+    int rp[IPG + 1];
+#pragma unroll
+    for (int i = 0; i <= IPG; ++i) rp[i] = bcast<LPR>(my_rp, i);
+    const int head = rp[0], tail = rp[IPG];
+
+    float acc[IPG][V][REP][VEC];
+#pragma unroll
+    for (int i = 0; i < IPG; ++i)
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+#pragma unroll
+            for (int r = 0; r < REP; ++r)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[i][v][r][e] = 0.0f;
+
+    const float *__restrict__ B = a.B;
+    const long K = a.K;
+
+    for (int base = head; base < tail; base += LPR) {
+        const int idx = base + lg;
+        int c = 0, tag = 0;
+        float av[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) av[v] = 0.0f;
+        if (idx < tail) {
+            c = stream_load(a.colidx + idx);
+            if constexpr (V == 1) {
+                av[0] = stream_load(a.val + idx);
+            } else {
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                const f2 t = stream_load(reinterpret_cast<const f2 *>(a.val) + idx);
+                av[0] = t[0];
+                av[1] = t[1];
+            }
+#pragma unroll
+            for (int i = 1; i < IPG; ++i) tag += (idx >= rp[i]);
+        }
+        const int cnt = min(LPR, tail - base);
+        for (int j = 0; j < cnt; j += U) {
+            int cj[U], tj[U];
+            float aj[U][V];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                cj[u] = bcast<LPR>(c, j + u);
+                tj[u] = bcast<LPR>(tag, j + u);
+#pragma unroll
+                for (int v = 0; v < V; ++v) aj[u][v] = bcast<LPR>(av[v], j + u);
+            }
+            float b[U][REP][VEC];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float *brow = B + (long)cj[u] * K;
+                const bool ok = j + u < cnt;
+#pragma unroll
+                for (int r = 0; r < REP; ++r) {
+                    if (ok && kv[r]) {
+                        load_vec<VEC>(brow + kc[r], b[u][r]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) b[u][r][e] = 0.0f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < IPG; ++i)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) {
+                        const float m = tj[u] == i ? aj[u][v] : 0.0f;
+#pragma unroll
+                        for (int r = 0; r < REP; ++r)
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e)
+                                acc[i][v][r][e] = fmaf(m, b[u][r][e], acc[i][v][r][e]);
+                    }
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < IPG; ++i) {
+        const long item = (long)item0 + i;
+        if (item < a.M) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const long row = item * V + v;
+                if (row < a.n_rows) {
+                    float *crow = a.C + row * K;
+#pragma unroll
+                    for (int r = 0; r < REP; ++r)
+                        if (kv[r]) store_vec<VEC>(crow + kc[r], acc[i][v][r]);
+                }
+            }
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) zero_panels_kernel(const int32_t *__restrict__ panels,
                                                           long n_panels, int V, float *C,
                                                           int n_rows, int K)
@@ -275,16 +435,63 @@ KernelFn pick(int V, int S, int lpr, int vec, int rep)
     return nullptr;
 }
 
+// batched instances exist where the accumulators stay within 32 registers
+template <int V, int LPR, int VEC, int REP> KernelFn pickb_ipg(int ipg)
+{
+    if constexpr (2 < LPR && V * VEC * REP * 2 <= 32)
+        if (ipg == 2) return &spmm_batched_kernel<V, LPR, VEC, REP, 2>;
+    if constexpr (4 < LPR && V * VEC * REP * 4 <= 32)
+        if (ipg == 4) return &spmm_batched_kernel<V, LPR, VEC, REP, 4>;
+    return nullptr;
+}
+template <int V, int LPR, int VEC> KernelFn pickb_rep(int rep, int ipg)
+{
+    switch (rep) {
+    case 1: return pickb_ipg<V, LPR, VEC, 1>(ipg);
+    case 2: return pickb_ipg<V, LPR, VEC, 2>(ipg);
+    case 4: return pickb_ipg<V, LPR, VEC, 4>(ipg);
+    }
+    return nullptr;
+}
+template <int V, int LPR> KernelFn pickb_vec(int vec, int rep, int ipg)
+{
+    switch (vec) {
+    case 1: return pickb_rep<V, LPR, 1>(rep, ipg);
+    case 2: return pickb_rep<V, LPR, 2>(rep, ipg);
+    case 4: return pickb_rep<V, LPR, 4>(rep, ipg);
+    }
+    return nullptr;
+}
+template <int V> KernelFn pickb_lpr(int lpr, int vec, int rep, int ipg)
+{
+    switch (lpr) {
+    case 4: return pickb_vec<V, 4>(vec, rep, ipg);
+    case 8: return pickb_vec<V, 8>(vec, rep, ipg);
+    case 16: return pickb_vec<V, 16>(vec, rep, ipg);
+    case 32: return pickb_vec<V, 32>(vec, rep, ipg);
+    case 64: return pickb_vec<V, 64>(vec, rep, ipg);
+    }
+    return nullptr;
+}
+KernelFn pick_any(int V, int S, int lpr, int vec, int rep, int ipg)
+{
+    if (ipg <= 1) return pick(V, S, lpr, vec, rep);
+    if (S) return nullptr;
+    if (V == 1) return pickb_lpr<1>(lpr, vec, rep, ipg);
+    if (V == 2) return pickb_lpr<2>(lpr, vec, rep, ipg);
+    return nullptr;
+}
+
 } // namespace
 
-bool kernel_exists(int V, int S, int lpr, int vec, int rep)
+bool kernel_exists(int V, int S, int lpr, int vec, int rep, int ipg)
 {
-    return pick(V, S, lpr, vec, rep) != nullptr;
+    return pick_any(V, S, lpr, vec, rep, ipg) != nullptr;
 }
 
 hipError_t launch_spmm(int V, int S, const LaunchShape &ls, const SpmmArgs &args, hipStream_t stream)
 {
-    KernelFn fn = pick(V, S, ls.lpr, ls.vec, ls.rep);
+    KernelFn fn = pick_any(V, S, ls.lpr, ls.vec, ls.rep, ls.ipg);
     if (!fn) return hipErrorInvalidValue;
     if (ls.grid_x <= 0 || ls.grid_y <= 0) return hipSuccess; // nothing to do
     hipLaunchKernelGGL(fn, dim3(ls.grid_x, ls.grid_y), dim3(64 * ls.waves), 0, stream, args);

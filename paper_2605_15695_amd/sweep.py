@@ -96,6 +96,9 @@ def main(argv=None) -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--formats", default="all", help="all | comma list of V:S:SG, e.g. 1:0:0,1:1:64")
     ap.add_argument("--no-hipsparse", action="store_true")
+    ap.add_argument("--shapes", default=None,
+                    help="explicit launch shapes instead of the enumeration: comma list of "
+                         "lanes:vec:rep:waves:items_per_group")
     args = ap.parse_args(argv)
 
     import torch
@@ -154,11 +157,19 @@ def main(argv=None) -> int:
             V, S, SG = fmt
             h = handles[fmt]
             waves_list = (2, 4) if args.quick else (1, 2, 4, 8)
-            for (lpr, vec, rep), waves, remap in itertools.product(kernel_shapes(K, args.quick), waves_list,
-                                                                   (1, 0)):
+            ipg_list = (1, 2, 4) if not S else (1,)
+            if args.shapes:
+                combos = [(tuple(int(x) for x in sh.split(":")[:3]), int(sh.split(":")[3]), 1,
+                           int(sh.split(":")[4])) for sh in args.shapes.split(",")]
+            else:
+                combos = itertools.product(kernel_shapes(K, args.quick), waves_list, (1, 0), ipg_list)
+            for (lpr, vec, rep), waves, remap, ipg in combos:
                 if args.quick and not remap:
                     continue
-                pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, 0 if remap else pc.PCSR_FLAG_NO_XCD_REMAP)
+                if ipg > 1 and S:
+                    continue
+                pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, ipg,
+                                          0 if remap else pc.PCSR_FLAG_NO_XCD_REMAP)
                 try:
                     q = pc.pcsr_query_launch(h, K)
                 except pc.PcsrError:
@@ -173,7 +184,7 @@ def main(argv=None) -> int:
                 else:
                     dev = float((Cd - Cref).abs().max().item()) / scale
                 rec = dict(base, kind="pcsr", V=V, S=S, SG=SG, lanes_per_row=lpr, vec=vec, rep=rep,
-                           waves_per_wg=waves, xcd_remap=remap, grid_x=q["grid_x"], grid_y=q["grid_y"],
+                           waves_per_wg=waves, items_per_group=ipg, xcd_remap=remap, grid_x=q["grid_x"], grid_y=q["grid_y"],
                            ms_median=med, ms_min=mn, gflops=flops / med / 1e6,
                            roofline_frac=bytes_min / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, max_rel_dev=dev)
                 emit(rec)
@@ -207,13 +218,29 @@ def main(argv=None) -> int:
                 if med < hs_best[0]:
                     hs_best = (med, rec)
                 print(f"[sweep] K={K} hipsparse {name}: {med:.4f} ms", flush=True)
-        summary = dict(base, kind="summary", pcsr_best=best[1], hipsparse_best=hs_best[1],
+        # the library's own pick (pcsr_select) for this input, timed like the others
+        sel = pc.pcsr_select(feats, K)
+        hsel = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, sel)
+        qs = pc.pcsr_query_launch(hsel, K)
+        Cd.fill_(float("nan"))
+        med, mn = time_launches(lambda: pc.pcsr_spmm(hsel, Bd, Cd, K, stream), stream, torch,
+                                args.warmup, args.reps)
+        dev = float((Cd - Cref).abs().max().item()) / scale if Cref is not None else None
+        selrec = dict(base, kind="selected", V=sel.V, S=sel.S, SG=sel.SG, **qs, ms_median=med, ms_min=mn,
+                      gflops=flops / med / 1e6, roofline_frac=bytes_min / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      max_rel_dev=dev, vs_sweep_best=(best[0] / med) if best[1] else None)
+        emit(selrec)
+        hsel.close()
+        print(f"[sweep] K={K} SELECTED V={sel.V} S={sel.S} SG={sel.SG} lpr={qs['lanes_per_row']} vec={qs['vec']} "
+              f"rep={qs['rep']} gy={qs['grid_y']} waves={qs['waves_per_wg']}: {med:.4f} ms "
+              f"({100 * best[0] / med:.1f}% of sweep best)", flush=True)
+        summary = dict(base, kind="summary", selected=selrec, pcsr_best=best[1], hipsparse_best=hs_best[1],
                        speedup_vs_hipsparse=(hs_best[0] / best[0]) if hs_best[1] and best[1] else None)
         emit(summary)
         b = best[1]
         print(f"[sweep] K={K} BEST {b['ms_median']:.4f} ms {b['gflops']:.0f} GFLOP/s roofline {b['roofline_frac']:.3f} "
               f"V={b['V']} S={b['S']} SG={b['SG']} lpr={b['lanes_per_row']} vec={b['vec']} rep={b['rep']} "
-              f"waves={b['waves_per_wg']} remap={b['xcd_remap']} | hipsparse best "
+              f"waves={b['waves_per_wg']} ipg={b['items_per_group']} remap={b['xcd_remap']} | hipsparse best "
               f"{hs_best[0]:.4f} ms ({hs_best[1]['alg'] if hs_best[1] else '-'})", flush=True)
         del Bd, Cd, Cref
         torch.cuda.empty_cache()

@@ -95,13 +95,62 @@ def test_every_kernel_variant(V, S):
         Bd, ref, bound = cache[K]
         waves = next(waves_cycle)
         print(f"case V={V} S={S} lpr={lpr} vec={vec} rep={rep} waves={waves} K={K}", flush=True)
-        pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, pc.PCSR_FLAG_NO_XCD_REMAP if rep == 2 else 0)
+        pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, flags=pc.PCSR_FLAG_NO_XCD_REMAP if rep == 2 else 0)
         q = pc.pcsr_query_launch(h, K)
         assert q["grid_y"] == 2
         Cd = torch.full((n, K), float("nan"), dtype=torch.float32, device="cuda")
         pc.pcsr_spmm(h, Bd, Cd, K)
         torch.cuda.synchronize()
         _check(Cd.cpu().numpy(), ref, bound, f"V={V} S={S} lpr={lpr} vec={vec} rep={rep}")
+    h.close()
+
+
+@pytest.mark.parametrize("name", ["sbm", "road"])
+@pytest.mark.parametrize("V", [1, 2])
+def test_batched_kernel_variants(name, V):
+    """items_per_group in {2, 4}: every instance, ragged K over two grid.y slices, odd row count."""
+    g0 = _graph(name)
+    n = g0.n_rows - 1
+    nnz = int(g0.rowptr[n])
+    g = synth.Graph(name + "_odd", n, g0.n_cols, g0.rowptr[:n + 1].copy(), g0.colidx[:nnz], g0.vals[:nnz])
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=0))
+    cache = {}
+    tested = 0
+    waves_cycle = itertools.cycle([1, 2, 4, 8])
+    for ipg, lpr, vec, rep in itertools.product([2, 4], [4, 8, 16, 32, 64], [1, 2, 4], [1, 2, 4]):
+        K = lpr * vec * rep + vec * 3
+        pc.pcsr_set_kernel_params(h, lpr, vec, rep, next(waves_cycle), ipg)
+        try:
+            q = pc.pcsr_query_launch(h, K)
+        except pc.PcsrError:
+            assert not (ipg < lpr and V * vec * rep * ipg <= 32)
+            continue
+        assert q["items_per_group"] == ipg and q["grid_y"] == 2
+        if K not in cache:
+            B = synth.dense_operand(g.n_cols, K, "normal", K)
+            cache[K] = (torch.from_numpy(B).cuda(),) + oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+        Bd, ref, bound = cache[K]
+        print(f"case {name} V={V} ipg={ipg} lpr={lpr} vec={vec} rep={rep} K={K}", flush=True)
+        Cd = torch.full((n, K), float("nan"), dtype=torch.float32, device="cuda")
+        pc.pcsr_spmm(h, Bd, Cd, K)
+        torch.cuda.synchronize()
+        _check(Cd.cpu().numpy(), ref, bound, f"{name} V={V} ipg={ipg} lpr={lpr} vec={vec} rep={rep}")
+        tested += 1
+    assert tested >= 30
+    h.close()
+
+
+def test_batched_kernel_refused_where_it_does_not_apply():
+    g = _graph("rmat20")                     # longest row > 1024
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=1, S=0))
+    pc.pcsr_set_kernel_params(h, items_per_group=2)
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_query_launch(h, 64)
+    h.close()
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=1, S=1, SG=64))
+    pc.pcsr_set_kernel_params(h, items_per_group=2)
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_query_launch(h, 64)
     h.close()
 
 
@@ -131,6 +180,8 @@ def test_tiny_adversarial_all_tuples(case):
         ref, bound = oracle.spmm(rp, ci, va, B)
         for V, S, SG in [(1, 0, 0), (2, 0, 0), (1, 1, 0), (2, 1, 0), (1, 1, 3), (2, 1, 3), (1, 1, 64)]:
             kernels = [None, (4, 0, 0, 1), (64, 0, 1, 2), (16, 1, 2, 8)]
+            if not S:
+                kernels += [(8, 0, 1, 2, 4), (64, 0, 0, 1, 2)]
             for kern in kernels:
                 print(f"case {case} K={K} V={V} S={S} SG={SG} kernel={kern}", flush=True)
                 C = _spmm(g, B, pc.make_params(V=V, S=S, SG=SG), K, kernel=kern)

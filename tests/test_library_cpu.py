@@ -145,6 +145,14 @@ def test_launch_resolution():
         pc.pcsr_query_launch(h, 33)          # vec = 2 does not divide 33
     with pytest.raises(pc.PcsrError):
         pc.pcsr_set_kernel_params(h, 5, 0, 0, 0)
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_set_kernel_params(h, items_per_group=3)
+    pc.pcsr_set_kernel_params(h, 32, 4, 1, 4, 4)
+    q = pc.pcsr_query_launch(h, 128)
+    assert q["items_per_group"] == 4 and q["grid_x"] == -(-g.n_rows // (4 * 2 * 4))
+    pc.pcsr_set_kernel_params(h, 4, 4, 1, 4, 4)          # items_per_group must be < lanes_per_row
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_query_launch(h, 16)
 
 
 def test_select_returns_valid_tuple():
