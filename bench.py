@@ -21,6 +21,12 @@ import time
 import numpy as np
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per SpMM launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
+# each scaled by what the counter reads for a plain copy kernel of known size); the
+# summaries with the commands are under profiles/.  Keyed by (workload, K).
+PROFILED_TRAFFIC = {
+    ("road-full", 128): 2_121_501_891,   # profiles/spmm_road_K128.md
+}
 
 
 def algorithmic_bytes(g, K: int) -> int:
@@ -144,7 +150,8 @@ def main() -> int:
         "config": {"workload": f"{args.workload}-{args.size}", "graph": g.name, "n": g.n_rows,
                    "nnz": g.nnz, "K": K, "V": V, "S": S, **launch},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": PROFILED_TRAFFIC.get((f"{args.workload}-{args.size}", K)),
                      "kernel_ms_mean": kern_ms, "kernel_ms_median": statistics.median(per_launch_ms),
                      "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": bytes_min},
         "setup": {"generate_s": gen_s, "features_select_ms": feat_ms, "pcsr_build_ms": build_ms},
