@@ -52,6 +52,10 @@ def main() -> int:
     ap.add_argument("--rep", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--items-per-group", type=int, default=0)
+    ap.add_argument("--col-window", type=int, default=-1, help="-1 = library selector")
+    ap.add_argument("--reorder", action="store_true",
+                    help="apply the library's locality reordering first (A' = P A P^T, B' = P B); the timed "
+                         "SpMM runs on the relabelled problem and its result is checked as C = P^T C'")
     ap.add_argument("--no-xcd-remap", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
@@ -81,6 +85,17 @@ def main() -> int:
     B = synth.dense_operand(g.n_cols, K, spec["B"], 2)
     gen_s = time.time() - t0
 
+    perm, reorder_ms = None, None
+    g_orig, B_orig = g, B
+    if args.reorder:
+        t0 = time.time()
+        perm, n_clusters = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
+        rp, ci, va = pc.pcsr_permute_csr(g.n_rows, g.rowptr, g.colidx, g.vals, perm)
+        reorder_ms = (time.time() - t0) * 1e3
+        g = synth.Graph(g.name + "_reordered", g.n_rows, g.n_cols, rp, ci, va)
+        B = np.empty_like(B_orig)
+        B[perm] = B_orig
+
     t0 = time.time()
     feats = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
     sel = pc.pcsr_select(feats, K)
@@ -93,6 +108,7 @@ def main() -> int:
         lanes_per_row=args.lanes_per_row or sel.lanes_per_row, vec=args.vec or sel.vec,
         rep=args.rep or sel.rep, waves_per_wg=args.waves or sel.waves_per_wg,
         items_per_group=args.items_per_group or sel.items_per_group,
+        col_window=sel.col_window if args.col_window < 0 else args.col_window,
         flags=pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
     t0 = time.time()
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, params)
@@ -147,14 +163,16 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}-{args.size}", "graph": g.name, "n": g.n_rows,
+        "config": {"workload": f"{args.workload}-{args.size}" + ("+reorder" if args.reorder else ""),
+                   "graph": g.name, "n": g.n_rows,
                    "nnz": g.nnz, "K": K, "V": V, "S": S, **launch},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": PROFILED_TRAFFIC.get((f"{args.workload}-{args.size}", K)),
                      "kernel_ms_mean": kern_ms, "kernel_ms_median": statistics.median(per_launch_ms),
                      "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": bytes_min},
-        "setup": {"generate_s": gen_s, "features_select_ms": feat_ms, "pcsr_build_ms": build_ms},
+        "setup": {"generate_s": gen_s, "features_select_ms": feat_ms, "pcsr_build_ms": build_ms,
+                  "reorder_ms": reorder_ms},
     }
 
     if not args.no_check or not args.no_cpu_baseline:
@@ -172,16 +190,20 @@ def main() -> int:
         for _ in range(reps):
             t0 = time.perf_counter()
             if rows is None:
-                ref, bound = oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+                ref, bound = oracle.spmm(g_orig.rowptr, g_orig.colidx, g_orig.vals, B_orig)
             else:
-                ref, bound = oracle.spmm_rows(g.rowptr, g.colidx, g.vals, B, rows)
+                ref, bound = oracle.spmm_rows(g_orig.rowptr, g_orig.colidx, g_orig.vals, B_orig, rows)
             best = min(best, time.perf_counter() - t0)
+        # row i of the original problem is row perm[i] of the relabelled one
         if rows is None:
             cpu_flops = flops
             got = Cd.cpu().numpy()
+            if perm is not None:
+                got = got[perm]
         else:
-            cpu_flops = 2.0 * float(np.diff(g.rowptr.astype(np.int64))[rows].sum()) * K
-            got = Cd[torch.from_numpy(rows).cuda()].cpu().numpy()
+            cpu_flops = 2.0 * float(np.diff(g_orig.rowptr.astype(np.int64))[rows].sum()) * K
+            sel_rows = rows if perm is None else perm[rows].astype(np.int64)
+            got = Cd[torch.from_numpy(sel_rows).cuda()].cpu().numpy()
         ok, worst = oracle.within_tolerance(got, ref, bound)
         out["cpu_baseline"] = {"value": cpu_flops / best / 1e9, "unit": "GFLOP/s",
                                "cores": oracle.max_threads(), "kind": "oracle", "sample": sample}

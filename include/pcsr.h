@@ -48,13 +48,21 @@ enum {
  *     S      0/1 workload balancing (Section 3.2): cap every work item at SG vectors.
  *     SG     split granularity; 0 = Eq. (3) with `omega`, > 0 = use as given.
  *     omega  lane count used by Eq. (3); 0 = 64 (wavefront).  32 gives the paper's SG.
+ *     col_window  column-window blocking: 0 = off, else 256, 512, 1024 or 2048.  Work
+ *            items are grouped into blocks of col_window/2 consecutive items; for each
+ *            block the build picks the window of col_window consecutive columns that
+ *            holds most of its nonzeros.  The kernel stages that window of B (one
+ *            grid.y column slice of it) in LDS and gathers from there; nonzeros outside
+ *            the window are gathered from memory as usual.  The PCSR arrays themselves
+ *            do not change.  Needs S = 0 and col_window*lanes_per_row*vec*rep*4 bytes
+ *            of LDS <= 160 KiB at launch.
  *   Kernel parameters (launch shape only; the paper's F and W):
  *     lanes_per_row  lanes cooperating on one work item: 4, 8, 16, 32 or 64; 0 = auto.
  *     vec            fp32 values per lane per B load: 1, 2 or 4; must divide K; 0 = auto.
  *     rep            column tiles per lane (the coarsening factor F): 1, 2 or 4; 0 = auto.
  *                    One work item covers lanes_per_row*vec*rep columns of C per grid.y
  *                    slice; wider K is covered by more grid.y slices.
- *     waves_per_wg   wavefronts per workgroup (the paper's W): 1, 2, 4 or 8; 0 = auto.
+ *     waves_per_wg   wavefronts per workgroup (the paper's W): 1, 2, 4, 8 or 16; 0 = auto.
  *     items_per_group  consecutive work items one lane group walks in a single pass,
  *                    gathering for all of them before any result is needed: 1, 2 or 4;
  *                    0 = auto.  Values above 1 need S = 0, items_per_group <
@@ -73,7 +81,8 @@ typedef struct {
     int32_t waves_per_wg;
     int32_t flags;
     int32_t items_per_group;
-    int32_t reserved[2]; /* must be 0 */
+    int32_t col_window;
+    int32_t reserved[1]; /* must be 0 */
 } pcsr_params_t;
 
 typedef struct pcsr_handle_s *pcsr_handle_t;
@@ -126,11 +135,18 @@ int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, 
 
 /*
  * Reports the launch shape pcsr_spmm would use for width K with the handle's current
- * kernel parameters (after "auto" resolution): out[0..6] = lanes_per_row, vec, rep,
- * waves_per_wg, grid.x, grid.y, items_per_group.  Host memory.
- * Errors: INVALID_ARG, UNSUPPORTED.
+ * kernel parameters (after "auto" resolution): out[0..7] = lanes_per_row, vec, rep,
+ * waves_per_wg, grid.x, grid.y, items_per_group, dynamic LDS bytes (0 unless the
+ * column-window kernel runs).  Host memory.  Errors: INVALID_ARG, UNSUPPORTED.
  */
-int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[7]);
+int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[8]);
+
+/*
+ * Column-window blocking as built into the handle (host, fp64[3]): col_window, work
+ * items per block, fraction of nonzero vectors that fall inside their block's window
+ * (0 when col_window is off).  Errors: INVALID_ARG.
+ */
+int pcsr_window_stats(pcsr_handle_t h, double out[3]);
 
 /*
  * Copies the PCSR arrays (Section 4.2, "Data Representation") out of the handle for
@@ -160,6 +176,30 @@ int pcsr_features(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *ro
  * Errors: INVALID_ARG, UNSUPPORTED (K <= 0).
  */
 int pcsr_select(const double *features, int32_t K, pcsr_params_t *out);
+
+/*
+ * Locality reordering pre-step (Section 4.4: a community-based relabelling of the nodes
+ * is the default first step of the pipeline and is amortised over many SpMMs).  Own
+ * scheme: up to max_rounds (0 = 8) rounds of synchronous label propagation over the
+ * pattern of a square matrix, then clusters are numbered one after the other, members
+ * in their original order.  Deterministic.
+ *   rowptr int32[n+1], colidx int32[nnz]: host.  perm (host, int32[n]) receives the new
+ *   id of every node: perm[old] = new.  n_clusters (host, may be NULL) receives the
+ *   number of clusters found.
+ * The caller applies it: A' = P A P^T (pcsr_permute_csr), B' = P B, and reads C = P^T C'.
+ * Errors: INVALID_ARG, BAD_CSR (column >= n), TOO_LARGE, OOM.
+ */
+int pcsr_reorder(int64_t n, const int32_t *rowptr, const int32_t *colidx, int32_t max_rounds,
+                 int32_t *perm, int64_t *n_clusters);
+
+/*
+ * Symmetric relabelling of a square CSR matrix: row perm[i] of the output holds row i of
+ * the input with every column c replaced by perm[c], columns sorted ascending.
+ * All arrays host; outputs sized like the inputs (int32[n+1], int32[nnz], fp32[nnz]).
+ * Errors: INVALID_ARG (nulls, perm not a permutation), OOM.
+ */
+int pcsr_permute_csr(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                     const int32_t *perm, int32_t *out_rowptr, int32_t *out_colidx, float *out_vals);
 
 /* MAC-job gap of Eq. (1) for width dim, coarsening F and lane count omega (0 when dim
  * is a multiple of F*omega, as Table 2 prints).  Returns -1 on non-positive input. */

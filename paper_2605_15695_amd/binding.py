@@ -25,8 +25,8 @@ FEATURE_NAMES = ("n", "n_hat", "nnz", "delta", "d", "d_hat", "d_max", "CV", "CV_
 class pcsr_params_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("V", "S", "SG", "omega", "lanes_per_row", "vec", "rep", "waves_per_wg", "flags",
-                 "items_per_group")]
-    _fields_ += [("reserved", ctypes.c_int32 * 2)]
+                 "items_per_group", "col_window")]
+    _fields_ += [("reserved", ctypes.c_int32 * 1)]
 
 
 class PcsrError(RuntimeError):
@@ -55,17 +55,21 @@ def _lib():
         lib.pcsr_spmm.argtypes = [vp, vp, vp, i32, vp]
         lib.pcsr_free.argtypes = [vp]
         lib.pcsr_set_kernel_params.argtypes = [vp, i32, i32, i32, i32, i32, i32]
-        lib.pcsr_query_launch.argtypes = [vp, i32, ctypes.POINTER(i32 * 7)]
+        lib.pcsr_query_launch.argtypes = [vp, i32, ctypes.POINTER(i32 * 8)]
+        lib.pcsr_window_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_double * 3)]
         lib.pcsr_export.argtypes = [vp, ctypes.POINTER(i64 * 6), vp, vp, vp, vp]
         lib.pcsr_features.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32]
         lib.pcsr_select.argtypes = [vp, i32, pp]
+        lib.pcsr_reorder.argtypes = [i64, vp, vp, i32, vp, ctypes.POINTER(i64)]
+        lib.pcsr_permute_csr.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
         lib.pcsr_mac_job_gap.argtypes = [i32, i32, i32]
         lib.pcsr_mac_job_gap.restype = i32
         lib.pcsr_strerror.argtypes = [ctypes.c_int]
         lib.pcsr_strerror.restype = ctypes.c_char_p
         lib.pcsr_last_hip_error.restype = ctypes.c_int
         for name in ("pcsr_build", "pcsr_spmm", "pcsr_free", "pcsr_set_kernel_params",
-                     "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select"):
+                     "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select",
+                     "pcsr_window_stats", "pcsr_reorder", "pcsr_permute_csr"):
             getattr(lib, name).restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -89,11 +93,12 @@ def _ptr(a, dtype=None):
 
 
 def make_params(V=1, S=0, SG=0, omega=0, lanes_per_row=0, vec=0, rep=0, waves_per_wg=0, flags=0,
-                items_per_group=0):
+                items_per_group=0, col_window=0):
     p = pcsr_params_t()
     p.V, p.S, p.SG, p.omega = V, int(S), SG, omega
     p.lanes_per_row, p.vec, p.rep, p.waves_per_wg, p.flags = lanes_per_row, vec, rep, waves_per_wg, flags
     p.items_per_group = items_per_group
+    p.col_window = col_window
     return p
 
 
@@ -165,12 +170,20 @@ def pcsr_set_kernel_params(h: Handle, lanes_per_row=0, vec=0, rep=0, waves_per_w
 
 
 def pcsr_query_launch(h: Handle, K: int) -> dict:
-    out = (ctypes.c_int32 * 7)()
+    out = (ctypes.c_int32 * 8)()
     rc = _lib().pcsr_query_launch(h.raw, K, ctypes.byref(out))
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_query_launch")
-    return dict(zip(("lanes_per_row", "vec", "rep", "waves_per_wg", "grid_x", "grid_y", "items_per_group"),
-                    list(out)))
+    return dict(zip(("lanes_per_row", "vec", "rep", "waves_per_wg", "grid_x", "grid_y", "items_per_group",
+                     "lds_bytes"), list(out)))
+
+
+def pcsr_window_stats(h: Handle) -> dict:
+    out = (ctypes.c_double * 3)()
+    rc = _lib().pcsr_window_stats(h.raw, ctypes.byref(out))
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_window_stats")
+    return dict(col_window=int(out[0]), items_per_block=int(out[1]), hit_fraction=float(out[2]))
 
 
 def pcsr_export(h: Handle) -> dict:
@@ -210,6 +223,35 @@ def pcsr_select(features, K: int) -> pcsr_params_t:
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_select")
     return p
+
+
+def pcsr_reorder(n, rowptr, colidx, max_rounds=0):
+    """Returns (perm int32[n] with perm[old] = new, number of clusters)."""
+    k0, p_r, _ = _ptr(rowptr, np.dtype(np.int32))
+    k1, p_c, _ = _ptr(colidx, np.dtype(np.int32))
+    perm = np.empty(n, np.int32)
+    ncl = ctypes.c_int64(0)
+    rc = _lib().pcsr_reorder(n, p_r, p_c, max_rounds, perm.ctypes.data, ctypes.byref(ncl))
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_reorder")
+    return perm, int(ncl.value)
+
+
+def pcsr_permute_csr(n, rowptr, colidx, vals, perm):
+    """Symmetric relabelling P A P^T; returns (rowptr, colidx, vals) of the relabelled matrix."""
+    k0, p_r, _ = _ptr(rowptr, np.dtype(np.int32))
+    k1, p_c, _ = _ptr(colidx, np.dtype(np.int32))
+    k2, p_v, _ = _ptr(vals, np.dtype(np.float32))
+    k3, p_p, _ = _ptr(perm, np.dtype(np.int32))
+    if int(k3.shape[0]) != n:
+        raise ValueError("perm must have n entries")
+    o_r = np.empty(n + 1, np.int32)
+    o_c = np.empty(k1.shape[0], np.int32)
+    o_v = np.empty(k1.shape[0], np.float32)
+    rc = _lib().pcsr_permute_csr(n, p_r, p_c, p_v, p_p, o_r.ctypes.data, o_c.ctypes.data, o_v.ctypes.data)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_permute_csr")
+    return o_r, o_c, o_v
 
 
 def pcsr_mac_job_gap(dim: int, F: int, omega: int) -> int:

@@ -1,6 +1,7 @@
 // C ABI of the PCSR SpMM library (see include/pcsr.h for the contract of each call).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -32,7 +33,8 @@ int check_kernel_params(int lpr, int vec, int rep, int waves, int ipg)
     if (lpr != 0 && !(is_pow2(lpr) && lpr >= 4 && lpr <= 64)) return PCSR_E_UNSUPPORTED;
     if (vec != 0 && vec != 1 && vec != 2 && vec != 4) return PCSR_E_UNSUPPORTED;
     if (rep != 0 && rep != 1 && rep != 2 && rep != 4) return PCSR_E_UNSUPPORTED;
-    if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return PCSR_E_UNSUPPORTED;
+    if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8 && waves != 16)
+        return PCSR_E_UNSUPPORTED;
     return PCSR_OK;
 }
 
@@ -48,6 +50,7 @@ struct pcsr_handle_s {
     float *d_val = nullptr;
     int32_t *d_trow = nullptr;
     int32_t *d_split = nullptr;
+    int32_t *d_win = nullptr;
     int64_t n_split = 0;
     int32_t lpr = 0, vec = 0, rep = 0, waves = 0, ipg = 0, flags = 0;
 };
@@ -63,7 +66,8 @@ void release_device(pcsr_handle_t h)
     if (h->d_val) (void)hipFree(h->d_val);
     if (h->d_trow) (void)hipFree(h->d_trow);
     if (h->d_split) (void)hipFree(h->d_split);
-    h->d_rowptr = h->d_colidx = h->d_trow = h->d_split = nullptr;
+    if (h->d_win) (void)hipFree(h->d_win);
+    h->d_rowptr = h->d_colidx = h->d_trow = h->d_split = h->d_win = nullptr;
     h->d_val = nullptr;
 }
 
@@ -92,6 +96,11 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
     int lpr = h->lpr;
     if (!lpr) {
         int need = (K + vec - 1) / vec;
+        if (h->host.win_cols > 0) {
+            // column window: the staged slice (win_cols rows of lanes*vec columns) gets 128 KiB
+            const int fit = (128 * 1024 / 4 / h->host.win_cols - 4) / vec;
+            if (need > fit) need = fit;
+        }
         lpr = 4;
         while (lpr < need && lpr < 64) lpr <<= 1;
     }
@@ -99,7 +108,8 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
     if (!rep) {
         int need = (K + lpr * vec - 1) / (lpr * vec);
         rep = 1;
-        while (rep < need && rep < 4) rep <<= 1;
+        if (h->host.win_cols == 0)
+            while (rep < need && rep < 4) rep <<= 1;
     }
     int waves = h->waves ? h->waves : 4;
     int ipg = h->ipg ? h->ipg : 1;
@@ -107,10 +117,34 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
         // the batched walk accumulates each item sequentially and has no atomic write-back
         if (h->host.S || h->host.max_item_len > 1024) return PCSR_E_UNSUPPORTED;
     }
-    if (!pcsr::kernel_exists(h->host.V, h->host.S, lpr, vec, rep, ipg)) return PCSR_E_UNSUPPORTED;
-    const int64_t items_per_wg = (int64_t)waves * (64 / lpr) * ipg;
-    const int64_t gx = (h->host.M + items_per_wg - 1) / items_per_wg;
     const int64_t tile = (int64_t)lpr * vec * rep;
+    ls->window = 0;
+    ls->lds_bytes = 0;
+    int64_t gx;
+    if (h->host.win_cols > 0) {
+        // column-window kernel: one workgroup per block of win_items work items
+        if (h->host.S || ipg > 1) return PCSR_E_UNSUPPORTED;
+        if (!pcsr::window_kernel_exists(h->host.V, lpr, vec, rep)) return PCSR_E_UNSUPPORTED;
+        const int64_t lds = (int64_t)h->host.win_cols * (tile + 4) * 4; // rows padded by 4 floats
+        if (lds > 160 * 1024) return PCSR_E_UNSUPPORTED;
+        if (!h->waves) waves = 16;
+        ls->window = 1;
+        ls->lds_bytes = (int32_t)lds;
+        gx = (h->host.M + h->host.win_items - 1) / h->host.win_items;
+    } else {
+        if (waves > 8) return PCSR_E_UNSUPPORTED;
+        if (!pcsr::kernel_exists(h->host.V, h->host.S, lpr, vec, rep, ipg)) return PCSR_E_UNSUPPORTED;
+        const int64_t items_per_wg = (int64_t)waves * (64 / lpr) * ipg;
+        if (h->flags & PCSR_FLAG_NO_XCD_REMAP) {
+            gx = (h->host.M + items_per_wg - 1) / items_per_wg;
+        } else {
+            // every XCD walks its own item range: 8 x the workgroups of the longest range
+            int64_t longest = 0;
+            for (int x = 0; x < 8; ++x)
+                longest = std::max<int64_t>(longest, h->host.xcd_bounds[x + 1] - h->host.xcd_bounds[x]);
+            gx = 8 * ((longest + items_per_wg - 1) / items_per_wg);
+        }
+    }
     const int64_t gy = (K + tile - 1) / tile;
     if (gx > 0x7fffffffLL || gy > 65535) return PCSR_E_TOO_LARGE;
     ls->lpr = lpr;
@@ -140,7 +174,11 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     if (prm.V != 1 && prm.V != 2) return PCSR_E_UNSUPPORTED;
     if (prm.S != 0 && prm.S != 1) return PCSR_E_UNSUPPORTED;
     if (prm.SG < 0 || prm.omega < 0) return PCSR_E_INVALID_ARG;
-    if (prm.reserved[0] || prm.reserved[1]) return PCSR_E_INVALID_ARG;
+    if (prm.reserved[0]) return PCSR_E_INVALID_ARG;
+    if (prm.col_window != 0 && prm.col_window != 256 && prm.col_window != 512 && prm.col_window != 1024 &&
+        prm.col_window != 2048)
+        return PCSR_E_UNSUPPORTED;
+    if (prm.col_window && prm.S) return PCSR_E_UNSUPPORTED;
     if (nnz >= (int64_t(1) << 31) || n_rows >= (int64_t(1) << 31) - 1 || n_cols >= (int64_t(1) << 31))
         return PCSR_E_TOO_LARGE;
     int rc = check_kernel_params(prm.lanes_per_row, prm.vec, prm.rep, prm.waves_per_wg, prm.items_per_group);
@@ -180,6 +218,13 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             delete h;
             return rc;
         }
+        if (prm.col_window) {
+            rc = pcsr::choose_windows(&h->host, prm.col_window);
+            if (rc != PCSR_OK) {
+                delete h;
+                return rc;
+            }
+        }
         h->host_only = host_only;
         h->lpr = prm.lanes_per_row;
         h->vec = prm.vec;
@@ -198,6 +243,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             if (rc == PCSR_OK) rc = upload(h->host.val, &h->d_val);
             if (rc == PCSR_OK && h->host.S) rc = upload(h->host.trow, &h->d_trow);
             if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_panels, &h->d_split);
+            if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_start, &h->d_win);
             if (rc != PCSR_OK) {
                 release_device(h);
                 delete h;
@@ -209,6 +255,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             std::vector<float>().swap(h->host.val);
             std::vector<int32_t>().swap(h->host.trow);
             std::vector<int32_t>().swap(h->host.split_panels);
+            std::vector<int32_t>().swap(h->host.win_start);
         }
         *out = h;
         return PCSR_OK;
@@ -250,6 +297,11 @@ int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream
     a.K = K;
     a.nblk = ls.grid_x;
     a.xcd_remap = (h->flags & PCSR_FLAG_NO_XCD_REMAP) ? 0 : 1;
+    for (int x = 0; x < 9; ++x) a.xb[x] = h->host.xcd_bounds[x];
+    a.win_start = h->d_win;
+    a.win_cols = h->host.win_cols;
+    a.win_items = h->host.win_items;
+    a.n_cols = (int32_t)h->host.n_cols;
     if (!hip_ok(pcsr::launch_spmm(h->host.V, h->host.S, ls, a, s))) return PCSR_E_HIP;
     return PCSR_OK;
 }
@@ -279,7 +331,7 @@ int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, 
     return PCSR_OK;
 }
 
-int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[7])
+int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[8])
 {
     if (!valid(h) || !out) return PCSR_E_INVALID_ARG;
     pcsr::LaunchShape ls;
@@ -292,6 +344,16 @@ int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[7])
     out[4] = ls.grid_x;
     out[5] = ls.grid_y;
     out[6] = ls.ipg;
+    out[7] = ls.lds_bytes;
+    return PCSR_OK;
+}
+
+int pcsr_window_stats(pcsr_handle_t h, double out[3])
+{
+    if (!valid(h) || !out) return PCSR_E_INVALID_ARG;
+    out[0] = (double)h->host.win_cols;
+    out[1] = (double)h->host.win_items;
+    out[2] = h->host.win_hit;
     return PCSR_OK;
 }
 

@@ -61,6 +61,8 @@ inline int64_t eq3_sg(int64_t nnz_v, int64_t nonempty, int64_t omega)
 
 } // namespace
 
+void balance_xcd_ranges(HostPcsr *hp);
+
 int validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
                  const int32_t *colidx)
 {
@@ -165,6 +167,7 @@ int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             int64_t mx = 0;
             for (int64_t p = 0; p < P; ++p) mx = std::max<int64_t>(mx, h.rowptr[p + 1] - h.rowptr[p]);
             h.max_item_len = mx;
+            balance_xcd_ranges(&h);
             return PCSR_OK;
         }
 
@@ -194,6 +197,79 @@ int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         });
         h.rowptr[M] = (int32_t)h.nnz_v;
         h.max_item_len = std::min<int64_t>(sg, h.nnz_v);
+        balance_xcd_ranges(&h);
+        return PCSR_OK;
+    } catch (const std::bad_alloc &) {
+        return PCSR_E_OOM;
+    }
+}
+
+void balance_xcd_ranges(HostPcsr *hp)
+{
+    HostPcsr &h = *hp;
+    constexpr int64_t kItemCost = 8; // launch + write-back of one item, in units of one vector
+    const int64_t M = h.M;
+    const int64_t total = (M ? (int64_t)h.rowptr[M] : 0) + kItemCost * M;
+    h.xcd_bounds[0] = 0;
+    for (int x = 1; x < 8; ++x) {
+        const int64_t target = total * x / 8;
+        // smallest i with rowptr[i] + kItemCost*i >= target (monotone in i)
+        int64_t lo = 0, hi = M;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) / 2;
+            if ((int64_t)h.rowptr[mid] + kItemCost * mid >= target)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        h.xcd_bounds[x] = (int32_t)lo;
+    }
+    h.xcd_bounds[8] = (int32_t)M;
+}
+
+int choose_windows(HostPcsr *hp, int32_t win_cols)
+{
+    HostPcsr &h = *hp;
+    h.win_cols = win_cols;
+    h.win_items = win_cols / 2;
+    h.win_start.clear();
+    h.win_hit = 0.0;
+    if (win_cols <= 0) return PCSR_OK;
+    try {
+        const int64_t nb = ceildiv(h.M, h.win_items);
+        h.win_start.assign(nb, -1);
+        std::vector<int64_t> hits(nb, 0);
+        parallel_for(nb, 16, [&](int64_t lo, int64_t hi) {
+            std::vector<int32_t> cols;
+            for (int64_t b = lo; b < hi; ++b) {
+                const int64_t i0 = b * h.win_items, i1 = std::min<int64_t>(h.M, i0 + h.win_items);
+                const int64_t s = h.rowptr[i0], e = h.rowptr[i1];
+                if (e <= s) continue;
+                cols.assign(h.colidx.begin() + s, h.colidx.begin() + e);
+                std::sort(cols.begin(), cols.end());
+                // densest window of win_cols columns: two pointers over the sorted columns
+                int64_t best = 0, best_lo = 0, l = 0;
+                for (int64_t r = 0; r < (int64_t)cols.size(); ++r) {
+                    while (cols[r] - cols[l] >= win_cols) ++l;
+                    if (r - l + 1 > best) {
+                        best = r - l + 1;
+                        best_lo = l;
+                    }
+                }
+                // staging costs win_cols row reads: worth it from two uses per staged row
+                if (best >= 2 * (int64_t)win_cols) {
+                    int64_t c0 = cols[best_lo];
+                    c0 = std::min<int64_t>(c0, std::max<int64_t>(0, h.n_cols - win_cols));
+                    h.win_start[b] = (int32_t)c0;
+                    int64_t cnt = 0;
+                    for (int32_t c : cols) cnt += (c >= c0 && c < c0 + win_cols);
+                    hits[b] = cnt;
+                }
+            }
+        });
+        int64_t tot = 0;
+        for (int64_t v : hits) tot += v;
+        h.win_hit = h.nnz_v ? double(tot) / double(h.nnz_v) : 0.0;
         return PCSR_OK;
     } catch (const std::bad_alloc &) {
         return PCSR_E_OOM;

@@ -20,6 +20,15 @@ struct HostPcsr {
     // are cleared before the kernel accumulates into them.
     std::vector<int32_t> split_panels;
     int64_t max_item_len = 0;
+    // Not part of the format: item boundaries that cut the item sequence into 8 contiguous
+    // ranges of equal work (vectors plus a per-item overhead), one per XCD.
+    int32_t xcd_bounds[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    // Column-window blocking (not part of the format): items are grouped win_items at a
+    // time; win_start[b] is the first column of block b's LDS-resident window, or -1
+    // when no window is worth staging for that block.
+    int32_t win_cols = 0, win_items = 0;
+    std::vector<int32_t> win_start;
+    double win_hit = 0.0; // fraction of nonzero vectors that fall inside their window
 };
 
 // Returns PCSR_OK or PCSR_E_BAD_CSR / PCSR_E_TOO_LARGE / PCSR_E_INVALID_ARG.
@@ -30,6 +39,10 @@ int validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *row
 int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
                const int32_t *colidx, const float *vals, int32_t V, int32_t S, int32_t SG,
                int32_t omega, HostPcsr *out);
+
+// Picks, per block of win_cols/2 consecutive items, the window of win_cols consecutive
+// columns holding most of the block's vectors (needs h->rowptr / h->colidx on the host).
+int choose_windows(HostPcsr *h, int32_t win_cols);
 
 // Table 3 features in the order documented in pcsr.h.
 int features_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,

@@ -17,17 +17,26 @@ struct SpmmArgs {
     int32_t n_rows; // rows of C
     int32_t K;
     int32_t nblk;      // grid.x
-    int32_t xcd_remap; // 1: contiguous item ranges per XCD
+    int32_t xcd_remap; // 1: one contiguous, work-balanced item range per XCD
+    int32_t xb[9];     // item range [xb[x], xb[x+1]) of XCD x (xcd_remap only)
+    // column-window blocking (window kernel only)
+    const int32_t *win_start; // per item block: first column of the staged window or -1
+    int32_t win_cols;         // rows of B staged in LDS
+    int32_t win_items;        // work items per block (= per workgroup)
+    int32_t n_cols;
 };
 
 // Resolved launch shape.
 struct LaunchShape {
     int32_t lpr, vec, rep, waves;
     int32_t ipg; // work items per lane group (1 = one item per group)
+    int32_t window; // 1: column-window kernel (one workgroup per item block, B window in LDS)
+    int32_t lds_bytes;
     int32_t grid_x, grid_y;
 };
 
 bool kernel_exists(int V, int S, int lpr, int vec, int rep, int ipg);
+bool window_kernel_exists(int V, int lpr, int vec, int rep);
 
 // Enqueues the SpMM kernel <V,S,lpr,vec,rep> with `waves` wavefronts per workgroup.
 hipError_t launch_spmm(int V, int S, const LaunchShape &ls, const SpmmArgs &args,

@@ -104,17 +104,18 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int waves = blockDim.x >> 6;
-    int bid = blockIdx.x;
+    // Consecutive workgroup ids go round-robin over the 8 XCDs.  With xcd_remap each XCD
+    // walks its own contiguous range of work items (ranges hold equal work, not equal
+    // item counts), so neighbouring rows share one L2.
+    long item_l = ((long)blockIdx.x * waves + wave) * G + (lane / LPR);
+    int limit = a.M;
     if (a.xcd_remap) {
-        // consecutive workgroup ids go round-robin over the 8 XCDs; hand each XCD one
-        // contiguous range of work items so neighbouring rows share an L2
-        const int x = bid & 7, idx = bid >> 3;
-        const int q = a.nblk >> 3, r = a.nblk & 7;
-        bid = x * q + (x < r ? x : r) + idx;
+        const int x = blockIdx.x & 7;
+        item_l = a.xb[x] + ((long)(blockIdx.x >> 3) * waves + wave) * G + (lane / LPR);
+        limit = a.xb[x + 1];
     }
     const int lg = lane & (LPR - 1);
-    const long item_l = ((long)bid * waves + wave) * G + (lane / LPR);
-    if (item_l >= a.M) return;
+    if (item_l >= limit) return;
     const int item = (int)item_l;
 
     const int kbase = blockIdx.y * (LPR * VEC * REP);
@@ -262,15 +263,15 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int waves = blockDim.x >> 6;
-    int bid = blockIdx.x;
-    if (a.xcd_remap) {
-        const int x = bid & 7, idx = bid >> 3;
-        const int q = a.nblk >> 3, r = a.nblk & 7;
-        bid = x * q + (x < r ? x : r) + idx;
+    long item0_l = (((long)blockIdx.x * waves + wave) * G + (lane / LPR)) * IPG;
+    int limit = a.M;
+    if (a.xcd_remap) { // work-balanced contiguous item range per XCD, as in spmm_kernel
+        const int x = blockIdx.x & 7;
+        item0_l = a.xb[x] + (((long)(blockIdx.x >> 3) * waves + wave) * G + (lane / LPR)) * IPG;
+        limit = a.xb[x + 1];
     }
     const int lg = lane & (LPR - 1);
-    const long item0_l = (((long)bid * waves + wave) * G + (lane / LPR)) * IPG;
-    if (item0_l >= a.M) return;
+    if (item0_l >= limit) return;
     const int item0 = (int)item0_l;
 
     const int kbase = blockIdx.y * (LPR * VEC * REP);
@@ -284,7 +285,7 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
 
     // item boundaries: lane i of the group fetches rowPtr[item0 + i], i <= IPG
     const int bsel = item0 + (lg < IPG ? lg : IPG);
-    const int my_rp = a.rowptr[bsel < a.M ? bsel : a.M];
+    const int my_rp = a.rowptr[bsel < limit ? bsel : limit];
     int rp[IPG + 1];
 #pragma unroll
     for (int i = 0; i <= IPG; ++i) rp[i] = bcast<LPR>(my_rp, i);
@@ -367,7 +368,7 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
 #pragma unroll
     for (int i = 0; i < IPG; ++i) {
         const long item = (long)item0 + i;
-        if (item < a.M) {
+        if (item < limit) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const long row = item * V + v;
@@ -377,6 +378,172 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
                     for (int r = 0; r < REP; ++r)
                         if (kv[r]) store_vec<VEC>(crow + kc[r], acc[i][v][r]);
                 }
+            }
+        }
+    }
+}
+
+// Column-window kernel (no balancing): one workgroup owns a block of win_items consecutive
+// work items and one grid.y column slice.  It first copies rows [c0, c0 + win_cols) of
+// that B slice into LDS (c0 chosen at build time as the densest window of the block's
+// columns), then walks its items like spmm_kernel, taking each B segment from LDS when
+// the column falls inside the window and from memory otherwise.  On clustered matrices
+// most gathers then cost LDS bandwidth instead of L1/L2 bandwidth.
+template <int V, int LPR, int VEC, int REP>
+__global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
+{
+    extern __shared__ __align__(16) float lds[];
+    constexpr int G = 64 / LPR;
+    constexpr int TW = LPR * VEC * REP; // columns per slice
+    constexpr int LW = TW + 4;          // floats per staged row, padded so rows start on different banks
+    constexpr int U0 = 16 / (REP * VEC);
+    constexpr int U = U0 < 1 ? 1 : (U0 > 8 ? 8 : (U0 > LPR ? LPR : U0));
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int waves = blockDim.x >> 6;
+    int bid = blockIdx.x;
+    if (a.xcd_remap) {
+        const int x = bid & 7, idx = bid >> 3;
+        const int q = a.nblk >> 3, r = a.nblk & 7;
+        bid = x * q + (x < r ? x : r) + idx;
+    }
+    const int lg = lane & (LPR - 1);
+    const int kbase = blockIdx.y * TW;
+    const float *__restrict__ B = a.B;
+    const long K = a.K;
+
+    const int c0 = a.win_start[bid];
+    const bool has_win = c0 >= 0;
+    if (has_win) { // uniform over the workgroup
+        constexpr int VPR = TW / VEC; // vector loads per staged row
+        const int total = a.win_cols * VPR;
+        for (int q = tid; q < total; q += blockDim.x) {
+            const int r = q / VPR;
+            const int e = (q - r * VPR) * VEC;
+            const int col = c0 + r;
+            float t[VEC];
+            if (col < a.n_cols && kbase + e < a.K) {
+                load_vec<VEC>(B + (long)col * K + kbase + e, t);
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) t[i] = 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) lds[r * LW + e + i] = t[i];
+        }
+        __syncthreads();
+    }
+
+    int kl[REP]; // column offset inside the slice
+    bool kv[REP];
+#pragma unroll
+    for (int r = 0; r < REP; ++r) {
+        kl[r] = (r * LPR + lg) * VEC;
+        kv[r] = kbase + kl[r] < a.K;
+    }
+
+    const int item_begin = bid * a.win_items;
+    const int item_end = min(a.M, item_begin + a.win_items);
+    for (int item = item_begin + wave * G + lane / LPR; item < item_end; item += waves * G) {
+        int head = a.rowptr[item];
+        int tail = a.rowptr[item + 1];
+        if constexpr (LPR == 64) {
+            head = __builtin_amdgcn_readfirstlane(head);
+            tail = __builtin_amdgcn_readfirstlane(tail);
+        }
+        float acc[V][REP][VEC];
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+#pragma unroll
+            for (int r = 0; r < REP; ++r)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[v][r][e] = 0.0f;
+
+        for (int base = head; base < tail; base += LPR) {
+            const int idx = base + lg;
+            int c = 0;
+            float av[V];
+#pragma unroll
+            for (int v = 0; v < V; ++v) av[v] = 0.0f;
+            if (idx < tail) {
+                c = stream_load(a.colidx + idx);
+                if constexpr (V == 1) {
+                    av[0] = stream_load(a.val + idx);
+                } else {
+                    typedef float f2 __attribute__((ext_vector_type(2)));
+                    const f2 t = stream_load(reinterpret_cast<const f2 *>(a.val) + idx);
+                    av[0] = t[0];
+                    av[1] = t[1];
+                }
+            }
+            const int cnt = min(LPR, tail - base);
+            float part[V][REP][VEC];
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+#pragma unroll
+                for (int r = 0; r < REP; ++r)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) part[v][r][e] = 0.0f;
+
+            for (int j = 0; j < cnt; j += U) {
+                int cj[U];
+                float aj[U][V];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    cj[u] = bcast<LPR>(c, j + u);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) aj[u][v] = bcast<LPR>(av[v], j + u);
+                }
+                float b[U][REP][VEC];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const bool ok = j + u < cnt;
+                    const unsigned off = (unsigned)(cj[u] - c0);
+                    const bool inw = has_win && off < (unsigned)a.win_cols;
+                    const float *brow = B + (long)cj[u] * K + kbase;
+                    const float *lrow = lds + off * LW;
+#pragma unroll
+                    for (int r = 0; r < REP; ++r) {
+                        if (ok && kv[r]) {
+                            if (inw) {
+#pragma unroll
+                                for (int e = 0; e < VEC; ++e) b[u][r][e] = lrow[kl[r] + e];
+                            } else {
+                                load_vec<VEC>(brow + kl[r], b[u][r]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) b[u][r][e] = 0.0f;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int r = 0; r < REP; ++r)
+#pragma unroll
+                        for (int v = 0; v < V; ++v)
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e)
+                                part[v][r][e] = fmaf(aj[u][v], b[u][r][e], part[v][r][e]);
+            }
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+#pragma unroll
+                for (int r = 0; r < REP; ++r)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) acc[v][r][e] += part[v][r][e];
+        }
+
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const long row = (long)item * V + v;
+            if (row < a.n_rows) {
+                float *crow = a.C + row * K + kbase;
+#pragma unroll
+                for (int r = 0; r < REP; ++r)
+                    if (kv[r]) store_vec<VEC>(crow + kl[r], acc[v][r]);
             }
         }
     }
@@ -482,7 +649,48 @@ KernelFn pick_any(int V, int S, int lpr, int vec, int rep, int ipg)
     return nullptr;
 }
 
+template <int V, int LPR, int VEC> KernelFn pickw_rep(int rep)
+{
+    switch (rep) {
+    case 1: return &spmm_window_kernel<V, LPR, VEC, 1>;
+    case 2: return &spmm_window_kernel<V, LPR, VEC, 2>;
+    case 4: return &spmm_window_kernel<V, LPR, VEC, 4>;
+    }
+    return nullptr;
+}
+template <int V, int LPR> KernelFn pickw_vec(int vec, int rep)
+{
+    switch (vec) {
+    case 1: return pickw_rep<V, LPR, 1>(rep);
+    case 2: return pickw_rep<V, LPR, 2>(rep);
+    case 4: return pickw_rep<V, LPR, 4>(rep);
+    }
+    return nullptr;
+}
+template <int V> KernelFn pickw_lpr(int lpr, int vec, int rep)
+{
+    switch (lpr) {
+    case 4: return pickw_vec<V, 4>(vec, rep);
+    case 8: return pickw_vec<V, 8>(vec, rep);
+    case 16: return pickw_vec<V, 16>(vec, rep);
+    case 32: return pickw_vec<V, 32>(vec, rep);
+    case 64: return pickw_vec<V, 64>(vec, rep);
+    }
+    return nullptr;
+}
+KernelFn pick_window(int V, int lpr, int vec, int rep)
+{
+    if (V == 1) return pickw_lpr<1>(lpr, vec, rep);
+    if (V == 2) return pickw_lpr<2>(lpr, vec, rep);
+    return nullptr;
+}
+
 } // namespace
+
+bool window_kernel_exists(int V, int lpr, int vec, int rep)
+{
+    return pick_window(V, lpr, vec, rep) != nullptr;
+}
 
 bool kernel_exists(int V, int S, int lpr, int vec, int rep, int ipg)
 {
@@ -491,9 +699,19 @@ bool kernel_exists(int V, int S, int lpr, int vec, int rep, int ipg)
 
 hipError_t launch_spmm(int V, int S, const LaunchShape &ls, const SpmmArgs &args, hipStream_t stream)
 {
+    if (ls.grid_x <= 0 || ls.grid_y <= 0) return hipSuccess; // nothing to do
+    if (ls.window) {
+        KernelFn fn = S ? nullptr : pick_window(V, ls.lpr, ls.vec, ls.rep);
+        if (!fn) return hipErrorInvalidValue;
+        // more than 64 KiB of dynamic LDS has to be allowed per kernel function
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, ls.lds_bytes);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(fn, dim3(ls.grid_x, ls.grid_y), dim3(64 * ls.waves), ls.lds_bytes, stream, args);
+        return hipGetLastError();
+    }
     KernelFn fn = pick_any(V, S, ls.lpr, ls.vec, ls.rep, ls.ipg);
     if (!fn) return hipErrorInvalidValue;
-    if (ls.grid_x <= 0 || ls.grid_y <= 0) return hipSuccess; // nothing to do
     hipLaunchKernelGGL(fn, dim3(ls.grid_x, ls.grid_y), dim3(64 * ls.waves), 0, stream, args);
     return hipGetLastError();
 }

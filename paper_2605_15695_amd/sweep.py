@@ -48,8 +48,8 @@ def kernel_shapes(K: int, quick: bool):
         for lpr in (4, 8, 16, 32, 64):
             for rep in (1, 2, 4):
                 tile = lpr * vec * rep
-                if tile * 2 < K:
-                    continue                      # more than two slices: A re-read too often
+                if tile * 8 < K or tile < 32 and tile < K:
+                    continue                      # too many slices: A re-read too often
                 if lpr * vec * (rep - 1) >= K:
                     continue                      # a whole repeat would be idle
                 if lpr * vec >= 2 * K and lpr > 4:
@@ -96,6 +96,8 @@ def main(argv=None) -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--formats", default="all", help="all | comma list of V:S:SG, e.g. 1:0:0,1:1:64")
     ap.add_argument("--no-hipsparse", action="store_true")
+    ap.add_argument("--reorder", action="store_true",
+                    help="sweep the matrix after the library's locality reordering (pcsr_reorder)")
     ap.add_argument("--shapes", default=None,
                     help="explicit launch shapes instead of the enumeration: comma list of "
                          "lanes:vec:rep:waves:items_per_group")
@@ -118,17 +120,25 @@ def main(argv=None) -> int:
     g = synth.workload(args.workload, args.size)
     spec = synth.WORKLOADS[args.workload]
     Ks = args.K or spec["K"]
-    feats = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
     print(f"[sweep] {args.workload}-{args.size}: n={g.n_rows} nnz={g.nnz} generated in {time.time()-t0:.1f}s",
           flush=True)
+    if args.reorder:
+        t0 = time.time()
+        perm, ncl = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
+        rp, ci, va = pc.pcsr_permute_csr(g.n_rows, g.rowptr, g.colidx, g.vals, perm)
+        g = synth.Graph(g.name + "_reordered", g.n_rows, g.n_cols, rp, ci, va)
+        print(f"[sweep] reordered into {ncl} clusters in {time.time()-t0:.2f}s", flush=True)
+    feats = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
     emit({"kind": "graph", "workload": args.workload, "size": args.size, "n": g.n_rows, "nnz": g.nnz,
           "features": dict(zip(pc.FEATURE_NAMES, map(float, feats)))})
 
     if args.formats == "all":
         sg_eq3 = 0
-        formats = [(1, 0, 0), (2, 0, 0), (1, 1, sg_eq3), (2, 1, sg_eq3), (1, 1, 256), (1, 1, 1024)]
+        formats = [(1, 0, 0), (2, 0, 0), (1, 1, sg_eq3), (2, 1, sg_eq3), (1, 1, 256), (1, 1, 1024),
+                   (1, 0, 0, 512), (1, 0, 0, 1024)]
     else:
         formats = [tuple(int(x) for x in f.split(":")) for f in args.formats.split(",")]
+    formats = [f if len(f) == 4 else f + (0,) for f in formats]      # (V, S, SG, col_window)
 
     d_rowptr = torch.from_numpy(g.rowptr).cuda()
     d_colidx = torch.from_numpy(g.colidx).cuda()
@@ -136,11 +146,14 @@ def main(argv=None) -> int:
 
     handles = {}
     for fmt in formats:
-        V, S, SG = fmt
+        V, S, SG, CW = fmt
         t0 = time.time()
         handles[fmt] = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals,
-                                     pc.make_params(V=V, S=S, SG=SG, flags=pc.PCSR_FLAG_NO_VALIDATE))
-        print(f"[sweep] built V={V} S={S} SG={SG} in {time.time()-t0:.2f}s", flush=True)
+                                     pc.make_params(V=V, S=S, SG=SG, col_window=CW,
+                                                    flags=pc.PCSR_FLAG_NO_VALIDATE))
+        hit = pc.pcsr_window_stats(handles[fmt])["hit_fraction"]
+        print(f"[sweep] built V={V} S={S} SG={SG} CW={CW} (window hit {hit:.3f}) in {time.time()-t0:.2f}s",
+              flush=True)
 
     for K in Ks:
         B = synth.dense_operand(g.n_cols, K, spec["B"], 2)
@@ -150,14 +163,18 @@ def main(argv=None) -> int:
         Cref = None
         flops = 2.0 * g.nnz * K
         bytes_min = algorithmic_bytes(g, K)
-        base = {"workload": args.workload, "size": args.size, "K": K, "nnz": g.nnz, "n": g.n_rows,
+        base = {"workload": args.workload + ("+reorder" if args.reorder else ""), "size": args.size, "K": K, "nnz": g.nnz, "n": g.n_rows,
                 "bytes_min": bytes_min}
         best = (float("inf"), None)
         for fmt in formats:
-            V, S, SG = fmt
+            V, S, SG, CW = fmt
             h = handles[fmt]
             waves_list = (2, 4) if args.quick else (1, 2, 4, 8)
             ipg_list = (1, 2, 4) if not S else (1,)
+            if CW:
+                if pc.pcsr_window_stats(h)["hit_fraction"] < 0.05:
+                    continue                      # no block has a window worth staging
+                waves_list, ipg_list = (8, 16), (1,)
             if args.shapes:
                 combos = [(tuple(int(x) for x in sh.split(":")[:3]), int(sh.split(":")[3]), 1,
                            int(sh.split(":")[4])) for sh in args.shapes.split(",")]
@@ -183,14 +200,14 @@ def main(argv=None) -> int:
                     dev = 0.0
                 else:
                     dev = float((Cd - Cref).abs().max().item()) / scale
-                rec = dict(base, kind="pcsr", V=V, S=S, SG=SG, lanes_per_row=lpr, vec=vec, rep=rep,
+                rec = dict(base, kind="pcsr", V=V, S=S, SG=SG, col_window=CW, lanes_per_row=lpr, vec=vec, rep=rep,
                            waves_per_wg=waves, items_per_group=ipg, xcd_remap=remap, grid_x=q["grid_x"], grid_y=q["grid_y"],
                            ms_median=med, ms_min=mn, gflops=flops / med / 1e6,
                            roofline_frac=bytes_min / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, max_rel_dev=dev)
                 emit(rec)
                 if med < best[0]:
                     best = (med, rec)
-            print(f"[sweep] K={K} V={V} S={S} SG={SG} done; best so far {best[0]:.4f} ms", flush=True)
+            print(f"[sweep] K={K} V={V} S={S} SG={SG} CW={CW} done; best so far {best[0]:.4f} ms", flush=True)
 
         hs_best = (float("inf"), None)
         if not args.no_hipsparse:
@@ -239,7 +256,7 @@ def main(argv=None) -> int:
         emit(summary)
         b = best[1]
         print(f"[sweep] K={K} BEST {b['ms_median']:.4f} ms {b['gflops']:.0f} GFLOP/s roofline {b['roofline_frac']:.3f} "
-              f"V={b['V']} S={b['S']} SG={b['SG']} lpr={b['lanes_per_row']} vec={b['vec']} rep={b['rep']} "
+              f"V={b['V']} S={b['S']} SG={b['SG']} CW={b['col_window']} lpr={b['lanes_per_row']} vec={b['vec']} rep={b['rep']} "
               f"waves={b['waves_per_wg']} ipg={b['items_per_group']} remap={b['xcd_remap']} | hipsparse best "
               f"{hs_best[0]:.4f} ms ({hs_best[1]['alg'] if hs_best[1] else '-'})", flush=True)
         del Bd, Cd, Cref

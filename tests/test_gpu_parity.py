@@ -154,6 +154,57 @@ def test_batched_kernel_refused_where_it_does_not_apply():
     h.close()
 
 
+@pytest.mark.parametrize("name", ["sbm", "sbm_shuffled", "road", "poisson"])
+@pytest.mark.parametrize("V", [1, 2])
+@pytest.mark.parametrize("wc", [256, 1024])
+def test_column_window_kernel(name, V, wc):
+    """B window staged in LDS: clustered input (most gathers from LDS), shuffled and
+    road-like inputs (few or no windows), several slice shapes and workgroup sizes."""
+    g = _graph(name)
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, col_window=wc))
+    st = pc.pcsr_window_stats(h)
+    assert st["col_window"] == wc and st["items_per_block"] == wc // 2
+    if name == "sbm" and wc == 1024:
+        assert st["hit_fraction"] > 0.7
+    assert 0.0 <= st["hit_fraction"] <= 1.0
+    spec = synth.WORKLOADS[name]
+    for K, kern in [(64, None), (40, None), (256, None), (64, (8, 4, 1, 4)), (48, (16, 1, 2, 16)),
+                    (24, (4, 2, 1, 8))]:
+        if kern:
+            pc.pcsr_set_kernel_params(h, *kern)
+        else:
+            pc.pcsr_set_kernel_params(h)
+        q = pc.pcsr_query_launch(h, K)
+        assert 0 < q["lds_bytes"] <= 160 * 1024
+        B, ref, bound = _oracle(name, g, K, spec["B"])
+        print(f"case window {name} V={V} wc={wc} K={K} {q}", flush=True)
+        Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+        pc.pcsr_spmm(h, torch.from_numpy(B).cuda(), Cd, K)
+        torch.cuda.synchronize()
+        _check(Cd.cpu().numpy(), ref, bound, f"window {name} V={V} wc={wc} K={K} {kern}")
+    h.close()
+
+
+def test_column_window_edges():
+    """Window wider than the matrix, last block partly filled, odd row count with V = 2."""
+    rng = np.random.default_rng(11)
+    rp, ci, va, _ = random_csr(rng, 301, 200, 0.5)          # n_cols < col_window
+    g = synth.Graph("dense_small", 301, 200, rp, ci, va)
+    for V in (1, 2):
+        for K in (16, 36):
+            B = synth.dense_operand(200, K, "uniform", K)
+            ref, bound = oracle.spmm(rp, ci, va, B)
+            C = _spmm(g, B, pc.make_params(V=V, col_window=256), K)
+            _check(C, ref, bound, f"window edges V={V} K={K}")
+    h = pc.pcsr_build(301, 200, rp, ci, va, pc.make_params(col_window=256))
+    assert pc.pcsr_window_stats(h)["hit_fraction"] == 1.0
+    h.close()
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_build(301, 200, rp, ci, va, pc.make_params(S=1, col_window=256))
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_build(301, 200, rp, ci, va, pc.make_params(col_window=300))
+
+
 def _tiny_cases():
     rng = np.random.default_rng(3)
     cases = {}

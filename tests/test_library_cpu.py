@@ -105,7 +105,7 @@ def test_error_paths():
     _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(S=2))
     _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(lanes_per_row=3))
     _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(vec=3))
-    _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(waves_per_wg=16))
+    _expect(binding.PCSR_E_UNSUPPORTED, 2, 3, rp, ci, va, P(waves_per_wg=3))
     _expect(binding.PCSR_E_INVALID_ARG, 2, 3, rp, ci, va, P(SG=-1))
     # malformed CSR
     _expect(binding.PCSR_E_BAD_CSR, 2, 3, np.array([0, 3, 2], np.int32), ci, va, P())        # not monotone
@@ -117,7 +117,7 @@ def test_error_paths():
     _expect(binding.PCSR_E_BAD_CSR, 2, 3, rp, np.array([1, 1, 2], np.int32), va, P())        # duplicate
     # reserved must be zero
     p = P()
-    p.reserved[1] = 5
+    p.reserved[0] = 5
     _expect(binding.PCSR_E_INVALID_ARG, 2, 3, rp, ci, va, p)
     # SpMM on a host-only handle is refused, never silently computed elsewhere
     h = pc.pcsr_build(2, 3, rp, ci, va, P())
@@ -133,7 +133,12 @@ def test_launch_resolution():
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(flags=HOST))
     q = pc.pcsr_query_launch(h, 16)
     assert (q["lanes_per_row"], q["vec"], q["rep"]) == (4, 4, 1) and q["grid_y"] == 1
-    assert q["grid_x"] == -(-g.n_rows // (q["waves_per_wg"] * 16))
+    per_wg = q["waves_per_wg"] * 16
+    # one work-balanced item range per XCD: 8 x the workgroups of the longest range
+    assert q["grid_x"] % 8 == 0 and -(-g.n_rows // per_wg) <= q["grid_x"] <= -(-g.n_rows // per_wg) + 64
+    pc.pcsr_set_kernel_params(h, flags=pc.PCSR_FLAG_NO_XCD_REMAP)
+    assert pc.pcsr_query_launch(h, 16)["grid_x"] == -(-g.n_rows // per_wg)
+    pc.pcsr_set_kernel_params(h)
     q = pc.pcsr_query_launch(h, 512)
     assert q["lanes_per_row"] * q["vec"] * q["rep"] * q["grid_y"] >= 512
     q = pc.pcsr_query_launch(h, 33)
@@ -149,7 +154,8 @@ def test_launch_resolution():
         pc.pcsr_set_kernel_params(h, items_per_group=3)
     pc.pcsr_set_kernel_params(h, 32, 4, 1, 4, 4)
     q = pc.pcsr_query_launch(h, 128)
-    assert q["items_per_group"] == 4 and q["grid_x"] == -(-g.n_rows // (4 * 2 * 4))
+    assert q["items_per_group"] == 4 and q["grid_x"] % 8 == 0
+    assert -(-g.n_rows // (4 * 2 * 4)) <= q["grid_x"] <= -(-g.n_rows // (4 * 2 * 4)) + 64
     pc.pcsr_set_kernel_params(h, 4, 4, 1, 4, 4)          # items_per_group must be < lanes_per_row
     with pytest.raises(pc.PcsrError):
         pc.pcsr_query_launch(h, 16)
@@ -163,3 +169,38 @@ def test_select_returns_valid_tuple():
         assert p.V in (1, 2) and p.S in (0, 1)
     assert pc.pcsr_select(pc.pcsr_features(*(lambda g: (g.n_rows, g.n_cols, g.rowptr, g.colidx))(
         synth.workload("road", "small"))), 64).S == 0
+
+
+def test_reorder_is_a_permutation_and_recovers_planted_clusters():
+    g = synth.workload("sbm_shuffled", "small")          # 24 blocks of 500, ids shuffled
+    perm, ncl = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
+    assert np.array_equal(np.sort(perm), np.arange(g.n_rows))
+    assert ncl == 24
+    perm2, _ = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
+    assert np.array_equal(perm, perm2)                   # deterministic
+    rp, ci, va = pc.pcsr_permute_csr(g.n_rows, g.rowptr, g.colidx, g.vals, perm)
+    # the relabelled matrix is P A P^T: compare with scipy
+    import scipy.sparse as sp
+    A = sp.csr_matrix((g.vals, g.colidx, g.rowptr), shape=(g.n_rows, g.n_cols)).tocoo()
+    A2 = sp.csr_matrix((A.data, (perm[A.row], perm[A.col])), shape=A.shape)
+    A2.sort_indices()
+    assert np.array_equal(rp, A2.indptr) and np.array_equal(ci, A2.indices)
+    assert np.array_equal(va.view(np.uint32), A2.data.astype(np.float32).view(np.uint32))
+    # rows of one planted block end up contiguous: the average row bandwidth collapses
+    b_before = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)[12]
+    b_after = pc.pcsr_features(g.n_rows, g.n_cols, rp, ci)[12]
+    assert b_after < 0.8 * b_before
+    h = pc.pcsr_build(g.n_rows, g.n_cols, rp, ci, va, pc.make_params(col_window=1024, flags=HOST))
+    assert pc.pcsr_window_stats(h)["hit_fraction"] > 0.85
+
+
+def test_reorder_error_paths_and_degenerate_inputs():
+    perm, ncl = pc.pcsr_reorder(0, np.zeros(1, np.int32), np.zeros(0, np.int32))
+    assert perm.size == 0 and ncl == 0
+    perm, ncl = pc.pcsr_reorder(5, np.zeros(6, np.int32), np.zeros(0, np.int32))
+    assert np.array_equal(perm, np.arange(5)) and ncl == 5
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_reorder(2, np.array([0, 1, 2], np.int32), np.array([0, 5], np.int32))
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_permute_csr(2, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32),
+                            np.ones(2, np.float32), np.array([0, 0], np.int32))
