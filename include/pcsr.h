@@ -201,6 +201,15 @@ int pcsr_reorder(int64_t n, const int32_t *rowptr, const int32_t *colidx, int32_
 int pcsr_permute_csr(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *vals,
                      const int32_t *perm, int32_t *out_rowptr, int32_t *out_colidx, float *out_vals);
 
+/*
+ * CSR of the transpose (n_cols x n_rows), columns of every output row ascending; used
+ * for the backward pass dB = A^T dC when A is embedded in GNN training (Section 6.5).
+ * All arrays host; out_rowptr int32[n_cols+1], out_colidx int32[nnz], out_vals fp32[nnz].
+ * Errors: INVALID_ARG, BAD_CSR (column out of range), OOM.
+ */
+int pcsr_transpose_csr(int64_t n_rows, int64_t n_cols, const int32_t *rowptr, const int32_t *colidx,
+                       const float *vals, int32_t *out_rowptr, int32_t *out_colidx, float *out_vals);
+
 /* MAC-job gap of Eq. (1) for width dim, coarsening F and lane count omega (0 when dim
  * is a multiple of F*omega, as Table 2 prints).  Returns -1 on non-positive input. */
 int32_t pcsr_mac_job_gap(int32_t dim, int32_t F, int32_t omega);

@@ -62,6 +62,7 @@ def _lib():
         lib.pcsr_select.argtypes = [vp, i32, pp]
         lib.pcsr_reorder.argtypes = [i64, vp, vp, i32, vp, ctypes.POINTER(i64)]
         lib.pcsr_permute_csr.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
+        lib.pcsr_transpose_csr.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp]
         lib.pcsr_mac_job_gap.argtypes = [i32, i32, i32]
         lib.pcsr_mac_job_gap.restype = i32
         lib.pcsr_strerror.argtypes = [ctypes.c_int]
@@ -69,7 +70,7 @@ def _lib():
         lib.pcsr_last_hip_error.restype = ctypes.c_int
         for name in ("pcsr_build", "pcsr_spmm", "pcsr_free", "pcsr_set_kernel_params",
                      "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select",
-                     "pcsr_window_stats", "pcsr_reorder", "pcsr_permute_csr"):
+                     "pcsr_window_stats", "pcsr_reorder", "pcsr_permute_csr", "pcsr_transpose_csr"):
             getattr(lib, name).restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -251,6 +252,21 @@ def pcsr_permute_csr(n, rowptr, colidx, vals, perm):
     rc = _lib().pcsr_permute_csr(n, p_r, p_c, p_v, p_p, o_r.ctypes.data, o_c.ctypes.data, o_v.ctypes.data)
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_permute_csr")
+    return o_r, o_c, o_v
+
+
+def pcsr_transpose_csr(n_rows, n_cols, rowptr, colidx, vals):
+    """CSR of A^T; returns (rowptr int32[n_cols+1], colidx, vals)."""
+    k0, p_r, _ = _ptr(rowptr, np.dtype(np.int32))
+    k1, p_c, _ = _ptr(colidx, np.dtype(np.int32))
+    k2, p_v, _ = _ptr(vals, np.dtype(np.float32))
+    o_r = np.empty(n_cols + 1, np.int32)
+    o_c = np.empty(k1.shape[0], np.int32)
+    o_v = np.empty(k1.shape[0], np.float32)
+    rc = _lib().pcsr_transpose_csr(n_rows, n_cols, p_r, p_c, p_v, o_r.ctypes.data, o_c.ctypes.data,
+                                   o_v.ctypes.data)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_transpose_csr")
     return o_r, o_c, o_v
 
 

@@ -406,35 +406,25 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     std::memset(&p, 0, sizeof(p));
     const double n = f[0], nnz = f[2], d_hat = f[5], d_max = f[6], cv = f[7], rho = f[11];
     const double bw = f[12], pr2 = f[15];
-    const double n_cols = (rho > 0 && n > 0) ? nnz / (rho * n) : n;
 
     // Balancing (Section 3.2) pays when a few rows dwarf the average one.  On MI355X the
-    // recorded sweeps prefer items of 256 vectors over Eq. (3)'s value for such inputs.
+    // recorded sweeps prefer items far longer than Eq. (3)'s value for such inputs: 256
+    // vectors, and 1024 once the matrix is so large that even then the items outnumber
+    // the wave slots of the chip many times over.
     p.S = (cv > 1.5 && d_max > 256.0) ? 1 : 0;
-    p.SG = p.S ? 256 : 0;
+    p.SG = p.S ? (nnz >= 64.0 * 1048576.0 ? 1024 : 256) : 0;
     p.omega = 64;
     // Vector size 2 (Section 3.1) when adjacent rows share columns (low padding), and for
     // very short rows, where pairing rows doubles the gathers a lane group keeps in flight.
     p.V = (!p.S && (d_hat < 6.0 || (pr2 < 0.30 && d_hat >= 4.0))) ? 2 : 1;
 
+    // Launch shape: the widest vector load that divides K, one lane group spanning the
+    // whole row of C when it fits a wavefront, repeats beyond that.
     const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
-    // Column slice per grid.y: when B is far larger than the last-level cache and rows
-    // reference columns all over the matrix, narrower slices (processed one after the
-    // other) shrink the footprint of the frequently used B rows until it is cache
-    // resident.  A slice is never narrower than one 128-byte line.
-    int slice = K;
-    const double b_bytes = n_cols * (double)K * 4.0;
-    const bool scattered = n_cols > 0 && bw > 0.05 * n_cols;
-    if (scattered && b_bytes > 768.0 * 1048576.0) {
-        double cols = 512.0 * 1048576.0 / (n_cols * 4.0);
-        int w = 32;
-        while (w * 2 <= cols && w * 2 < K) w *= 2;
-        if (w < K && w % vec == 0) slice = w;
-    }
     int lpr = 4;
-    while (lpr * vec < slice && lpr < 64) lpr <<= 1;
+    while (lpr * vec < K && lpr < 64) lpr <<= 1;
     int rep = 1;
-    while (lpr * vec * rep < slice && rep < 4) rep <<= 1;
+    while (lpr * vec * rep < K && rep < 4) rep <<= 1;
     if (!p.S && p.V == 1 && d_hat < 8.0 && lpr >= 32 && rep == 1) {
         lpr >>= 1; // short rows: more rows per wavefront, two loads per lane
         rep = 2;
@@ -442,8 +432,14 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     p.lanes_per_row = lpr;
     p.vec = vec;
     p.rep = rep;
-    p.waves_per_wg = p.S ? 2 : (d_hat >= 16.0 ? 8 : 2);
+    // Workgroup size: single-wave groups retire independently, which suits items of very
+    // different lengths; long uniform rows like full workgroups; short rows sit between.
+    p.waves_per_wg = p.S ? 1 : (d_hat >= 16.0 ? 8 : 2);
     p.items_per_group = 1;
+    p.col_window = 0;
+    (void)n;
+    (void)rho;
+    (void)bw;
     *out = p;
     return PCSR_OK;
 }

@@ -168,4 +168,31 @@ int pcsr_permute_csr(int64_t n, const int32_t *rowptr, const int32_t *colidx, co
     }
 }
 
+int pcsr_transpose_csr(int64_t n_rows, int64_t n_cols, const int32_t *rowptr, const int32_t *colidx,
+                       const float *vals, int32_t *out_rowptr, int32_t *out_colidx, float *out_vals)
+{
+    if (n_rows < 0 || n_cols < 0 || !rowptr || !out_rowptr) return PCSR_E_INVALID_ARG;
+    const int64_t nnz = rowptr[n_rows];
+    if (nnz > 0 && (!colidx || !vals || !out_colidx || !out_vals)) return PCSR_E_INVALID_ARG;
+    try {
+        std::vector<int64_t> cnt(n_cols + 1, 0);
+        for (int64_t p = 0; p < nnz; ++p) {
+            if (colidx[p] < 0 || colidx[p] >= n_cols) return PCSR_E_BAD_CSR;
+            ++cnt[colidx[p] + 1];
+        }
+        for (int64_t c = 0; c < n_cols; ++c) cnt[c + 1] += cnt[c];
+        for (int64_t c = 0; c <= n_cols; ++c) out_rowptr[c] = (int32_t)cnt[c];
+        // rows are visited in ascending order, so every output row ends up sorted
+        for (int64_t i = 0; i < n_rows; ++i)
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+                const int64_t o = cnt[colidx[p]]++;
+                out_colidx[o] = (int32_t)i;
+                out_vals[o] = vals[p];
+            }
+        return PCSR_OK;
+    } catch (const std::bad_alloc &) {
+        return PCSR_E_OOM;
+    }
+}
+
 } // extern "C"

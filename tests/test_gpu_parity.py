@@ -333,3 +333,20 @@ def test_full_size_road_sampled_rows():
     # property that holds at any size: nothing left unwritten
     assert not torch.isnan(Cd).any().item()
     h.close()
+
+
+@pytest.mark.parametrize("K", [48, 80, 96, 112, 144, 160, 176, 208, 240])
+def test_widths_that_are_not_powers_of_two(K):
+    """The paper sweeps dim in steps of 16 (Section 6.2); widths that leave a MAC-job gap
+    (Eq. (1)) for every power-of-two tile must still be exact in every column."""
+    g = _graph("rmat20")
+    B, ref, bound = _oracle("rmat20", g, K, "normal")
+    for params, kern in [(pc.make_params(V=1, S=0), None), (pc.make_params(V=2, S=1, SG=32), None),
+                         (pc.make_params(V=1, S=1, SG=64), (8, 4, 1, 2)),     # several 32-column slices
+                         (pc.make_params(V=1, S=0), (4, 4, 4, 4))]:
+        C = _spmm(g, B, params, K, kernel=kern)
+        _check(C, ref, bound, f"K={K} {kern}")
+    f = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx)
+    sel = pc.pcsr_select(f, K)
+    C = _spmm(g, B, sel, K)
+    _check(C, ref, bound, f"K={K} selected")

@@ -204,3 +204,17 @@ def test_reorder_error_paths_and_degenerate_inputs():
     with pytest.raises(pc.PcsrError):
         pc.pcsr_permute_csr(2, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32),
                             np.ones(2, np.float32), np.array([0, 0], np.int32))
+
+
+def test_transpose_csr_host():
+    import scipy.sparse as sp
+    rng = np.random.default_rng(4)
+    rowptr, colidx, vals, dense = random_csr(rng, 13, 29, 0.3, empty_rows=(2,))
+    trp, tci, tva = pc.pcsr_transpose_csr(13, 29, rowptr, colidx, vals)
+    At = sp.csr_matrix(dense.T)
+    At.sort_indices()
+    assert np.array_equal(trp, At.indptr) and np.array_equal(tci, At.indices)
+    assert np.array_equal(tva, At.data)
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_transpose_csr(2, 2, np.array([0, 1, 2], np.int32), np.array([0, 7], np.int32),
+                              np.ones(2, np.float32))
