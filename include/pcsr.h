@@ -37,8 +37,11 @@ enum {
     PCSR_FLAG_DEVICE_CSR = 1,  /* rowptr/colidx/vals passed to pcsr_build are device pointers */
     PCSR_FLAG_NO_VALIDATE = 2, /* trust the CSR (skips the O(nnz) check)                      */
     PCSR_FLAG_NO_XCD_REMAP = 4,/* keep the hardware's round-robin workgroup -> XCD order      */
-    PCSR_FLAG_HOST_ONLY = 8    /* build the arrays on the host only (no GPU needed); the
+    PCSR_FLAG_HOST_ONLY = 8,   /* build the arrays on the host only (no GPU needed); the
                                   handle serves pcsr_export but not pcsr_spmm                 */
+    PCSR_FLAG_GPU_BUILD = 16   /* generate the PCSR arrays with GPU kernels (host CSR arrays
+                                  are uploaded first).  CSR arrays given in device memory are
+                                  always built this way.  Not available with col_window       */
 };
 
 /*

@@ -17,6 +17,7 @@ PCSR_OK = 0
 PCSR_E_INVALID_ARG, PCSR_E_BAD_CSR, PCSR_E_UNSUPPORTED = -1, -2, -3
 PCSR_E_TOO_LARGE, PCSR_E_OOM, PCSR_E_HIP = -4, -5, -6
 PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_NO_VALIDATE, PCSR_FLAG_NO_XCD_REMAP, PCSR_FLAG_HOST_ONLY = 1, 2, 4, 8
+PCSR_FLAG_GPU_BUILD = 16
 PCSR_N_FEATURES = 16
 FEATURE_NAMES = ("n", "n_hat", "nnz", "delta", "d", "d_hat", "d_max", "CV", "CV_hat",
                  "SR_1", "SR_2", "rho", "b", "b_max", "PR_1", "PR_2")

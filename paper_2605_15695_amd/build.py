@@ -17,7 +17,7 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argum
 # fp32 atomics as hardware instructions; packed fp32 instructions disabled
 DEVICE = ["--offload-arch=gfx950", "-munsafe-fp-atomics",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-SOURCES = ["pcsr_kernels.hip", "pcsr_api.cpp", "pcsr_host.cpp", "pcsr_reorder.cpp"]
+SOURCES = ["pcsr_kernels.hip", "pcsr_build_gpu.hip", "pcsr_api.cpp", "pcsr_host.cpp", "pcsr_reorder.cpp"]
 
 
 def _compile(src: str) -> pathlib.Path:

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../include/pcsr.h"
+#include "pcsr_build_gpu.h"
 #include "pcsr_host.h"
 #include "pcsr_kernels.h"
 
@@ -186,24 +187,86 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     const bool host_only = (prm.flags & PCSR_FLAG_HOST_ONLY) != 0;
     if (host_only && (prm.flags & PCSR_FLAG_DEVICE_CSR)) return PCSR_E_INVALID_ARG;
 
-    try {
-        // CSR arrays handed over in device memory are staged on the host first
-        std::vector<int32_t> s_rowptr, s_colidx;
-        std::vector<float> s_vals;
-        if (prm.flags & PCSR_FLAG_DEVICE_CSR) {
-            s_rowptr.resize(n_rows + 1);
-            s_colidx.resize(nnz);
-            s_vals.resize(nnz);
-            if (!hip_ok(hipMemcpy(s_rowptr.data(), rowptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToHost)))
+    const bool device_csr = (prm.flags & PCSR_FLAG_DEVICE_CSR) != 0;
+    if ((device_csr || (prm.flags & PCSR_FLAG_GPU_BUILD)) && !prm.col_window) {
+        if (host_only) return PCSR_E_INVALID_ARG;
+        // ---- PCSR generation on the GPU
+        int32_t *t_rowptr = nullptr, *t_colidx = nullptr;
+        float *t_vals = nullptr;
+        auto drop_tmp = [&] {
+            if (t_rowptr) (void)hipFree(t_rowptr);
+            if (t_colidx) (void)hipFree(t_colidx);
+            if (t_vals) (void)hipFree(t_vals);
+        };
+        if (!device_csr) {
+            bool ok = hip_ok(hipMalloc((void **)&t_rowptr, sizeof(int32_t) * (n_rows + 1))) &&
+                      hip_ok(hipMalloc((void **)&t_colidx, sizeof(int32_t) * (nnz + 1))) &&
+                      hip_ok(hipMalloc((void **)&t_vals, sizeof(float) * (nnz + 1))) &&
+                      hip_ok(hipMemcpy(t_rowptr, rowptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyHostToDevice)) &&
+                      (nnz == 0 ||
+                       (hip_ok(hipMemcpy(t_colidx, colidx, sizeof(int32_t) * nnz, hipMemcpyHostToDevice)) &&
+                        hip_ok(hipMemcpy(t_vals, vals, sizeof(float) * nnz, hipMemcpyHostToDevice))));
+            if (!ok) {
+                drop_tmp();
                 return PCSR_E_HIP;
-            if (nnz && !hip_ok(hipMemcpy(s_colidx.data(), colidx, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost)))
-                return PCSR_E_HIP;
-            if (nnz && !hip_ok(hipMemcpy(s_vals.data(), vals, sizeof(float) * nnz, hipMemcpyDeviceToHost)))
-                return PCSR_E_HIP;
-            rowptr = s_rowptr.data();
-            colidx = s_colidx.data();
-            vals = s_vals.data();
+            }
+            rowptr = t_rowptr;
+            colidx = t_colidx;
+            vals = t_vals;
         }
+        pcsr::DeviceBuild db;
+        int herr = 0;
+        rc = pcsr::build_device(n_rows, n_cols, nnz, rowptr, colidx, vals, prm.V, prm.S, prm.SG, prm.omega,
+                                !(prm.flags & PCSR_FLAG_NO_VALIDATE), &db, &herr);
+        drop_tmp();
+        if (rc != PCSR_OK) {
+            if (rc == PCSR_E_HIP) g_last_hip = herr;
+            return rc;
+        }
+        pcsr_handle_s *h = new (std::nothrow) pcsr_handle_s();
+        if (!h) {
+            (void)hipFree(db.rowptr);
+            (void)hipFree(db.colidx);
+            (void)hipFree(db.val);
+            if (db.trow) (void)hipFree(db.trow);
+            if (db.split) (void)hipFree(db.split);
+            return PCSR_E_OOM;
+        }
+        h->host.n_rows = n_rows;
+        h->host.n_cols = n_cols;
+        h->host.nnz = nnz;
+        h->host.V = prm.V;
+        h->host.S = prm.S;
+        h->host.P = db.P;
+        h->host.M = db.M;
+        h->host.nnz_v = db.nnz_v;
+        h->host.SG = db.SG;
+        h->host.max_item_len = db.max_item_len;
+        for (int x = 0; x < 9; ++x) h->host.xcd_bounds[x] = db.xcd_bounds[x];
+        h->d_rowptr = db.rowptr;
+        h->d_colidx = db.colidx;
+        h->d_val = db.val;
+        h->d_trow = db.trow;
+        h->d_split = db.split;
+        h->n_split = db.n_split;
+        h->lpr = prm.lanes_per_row;
+        h->vec = prm.vec;
+        h->rep = prm.rep;
+        h->waves = prm.waves_per_wg;
+        h->ipg = prm.items_per_group;
+        h->flags = prm.flags;
+        if (!hip_ok(hipGetDevice(&h->device))) {
+            release_device(h);
+            delete h;
+            return PCSR_E_HIP;
+        }
+        *out = h;
+        return PCSR_OK;
+    }
+
+    try {
+        // CSR arrays handed over in device memory are staged on the host first (only the
+        // column-window build still needs them there)
         if (!(prm.flags & PCSR_FLAG_NO_VALIDATE)) {
             rc = pcsr::validate_csr(n_rows, n_cols, nnz, rowptr, colidx);
             if (rc != PCSR_OK) return rc;

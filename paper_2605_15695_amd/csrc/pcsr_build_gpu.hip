@@ -1,0 +1,349 @@
+// PCSR generation on the GPU (Section 4.2, "PCSR Generation"): the same two steps as the
+// host builder - vectorised blocking into V x 1 nonzero vectors, then the optional
+// workload split - but with the CSR arrays already in device memory, so nothing crosses
+// PCIe except a handful of scalars.  The arrays it produces are bit-identical to the
+// host builder's.
+#include <hip/hip_runtime.h>
+#include <hipcub/hipcub.hpp>
+
+#include <cstdint>
+#include <cstring>
+
+#include "../../include/pcsr.h"
+#include "pcsr_build_gpu.h"
+
+namespace pcsr {
+namespace {
+
+constexpr int kThreads = 256;
+
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
+
+// one thread per row: monotone row pointer, columns in range and strictly ascending
+__global__ void validate_kernel(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                                const int32_t *colidx, int *bad)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_rows) return;
+    const int64_t s = rowptr[i], e = rowptr[i + 1];
+    if (s > e || s < 0 || e > nnz) {
+        *bad = 1;
+        return;
+    }
+    int64_t prev = -1;
+    for (int64_t p = s; p < e; ++p) {
+        const int64_t c = colidx[p];
+        if (c <= prev || c >= n_cols) {
+            *bad = 1;
+            return;
+        }
+        prev = c;
+    }
+}
+
+// V = 2: distinct columns in the union of rows 2p and 2p+1
+__global__ void count_union_kernel(int64_t P, int64_t n_rows, const int32_t *rowptr, const int32_t *colidx,
+                                   int32_t *cnt)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > P) return;
+    if (p == P) {
+        cnt[P] = 0; // scanned together with the panels: prow[P] becomes the total
+        return;
+    }
+    const int64_t r0 = 2 * p;
+    int64_t a = rowptr[r0], ae = rowptr[r0 + 1];
+    int64_t b = ae, be = (r0 + 1 < n_rows) ? rowptr[r0 + 2] : ae, n = 0;
+    while (a < ae && b < be) {
+        const int32_t ca = colidx[a], cb = colidx[b];
+        a += (ca <= cb);
+        b += (cb <= ca);
+        ++n;
+    }
+    cnt[p] = (int32_t)(n + (ae - a) + (be - b));
+}
+
+// V = 2: merge the two rows of a panel into vectors (ascending column, +0.0f padding)
+__global__ void fill_union_kernel(int64_t P, int64_t n_rows, const int32_t *rowptr, const int32_t *colidx,
+                                  const float *vals, const int32_t *prow, int32_t *out_col, float *out_val)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    const int64_t r0 = 2 * p;
+    int64_t a = rowptr[r0], ae = rowptr[r0 + 1];
+    int64_t b = ae, be = (r0 + 1 < n_rows) ? rowptr[r0 + 2] : ae;
+    int64_t o = prow[p];
+    while (a < ae || b < be) {
+        const int32_t ca = a < ae ? colidx[a] : INT32_MAX;
+        const int32_t cb = b < be ? colidx[b] : INT32_MAX;
+        const int32_t c = ca < cb ? ca : cb;
+        out_col[o] = c;
+        out_val[2 * o] = (ca == c) ? vals[a] : 0.0f;
+        out_val[2 * o + 1] = (cb == c) ? vals[b] : 0.0f;
+        a += (ca == c);
+        b += (cb == c);
+        ++o;
+    }
+}
+
+// stats[0] = non-empty panels, stats[1] = longest panel
+__global__ void panel_stats_kernel(int64_t P, const int32_t *prow, unsigned long long *nonempty, int *longest)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int len = 0;
+    if (p < P) len = prow[p + 1] - prow[p];
+    typedef hipcub::BlockReduce<int, kThreads> Reduce;
+    __shared__ typename Reduce::TempStorage t1, t2;
+    const int ne = Reduce(t1).Sum(len > 0 ? 1 : 0);
+    const int mx = Reduce(t2).Reduce(len, hipcub::Max());
+    if (threadIdx.x == 0) {
+        if (ne) atomicAdd(nonempty, (unsigned long long)ne);
+        if (mx) atomicMax(longest, mx);
+    }
+}
+
+// work items per panel: max(1, ceil(len / SG))
+__global__ void items_kernel(int64_t P, const int32_t *prow, int32_t sg, int32_t *items)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > P) return;
+    if (p == P) {
+        items[P] = 0;
+        return;
+    }
+    const int len = prow[p + 1] - prow[p];
+    const int it = (int)(((long)len + sg - 1) / sg);
+    items[p] = it > 1 ? it : 1;
+}
+
+// rewritten rowPtr, TRow, and the list of panels that own more than one item
+__global__ void split_fill_kernel(int64_t P, const int32_t *prow, const int32_t *first, int32_t sg,
+                                  int32_t *out_rowptr, int32_t *out_trow, int32_t *split_list,
+                                  int *n_split)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    int64_t start = prow[p];
+    const int i0 = first[p], i1 = first[p + 1];
+    for (int it = i0; it < i1; ++it) {
+        out_rowptr[it] = (int32_t)start;
+        out_trow[it] = (int32_t)p;
+        start += sg;
+    }
+    if (i1 - i0 > 1) split_list[atomicAdd(n_split, 1)] = (int32_t)p;
+    if (p == P - 1) out_rowptr[i1] = prow[P];
+}
+
+// 8 contiguous item ranges of equal work (vectors + 8 per item); same rule as the host builder
+__global__ void xcd_bounds_kernel(int32_t M, const int32_t *rowptr, int32_t *xb)
+{
+    const int x = threadIdx.x;
+    if (x > 8) return;
+    if (x == 0) {
+        xb[0] = 0;
+        return;
+    }
+    if (x == 8) {
+        xb[8] = M;
+        return;
+    }
+    const long total = (long)rowptr[M] + 8L * M;
+    const long target = total * x / 8;
+    long lo = 0, hi = M;
+    while (lo < hi) {
+        const long mid = (lo + hi) / 2;
+        if ((long)rowptr[mid] + 8L * mid >= target)
+            hi = mid;
+        else
+            lo = mid + 1;
+    }
+    xb[x] = (int32_t)lo;
+}
+
+struct Scratch { // frees everything it still owns on scope exit
+    void *p[32] = {};
+    int n = 0;
+    hipError_t alloc(void **out, size_t bytes)
+    {
+        if (n >= 32) return hipErrorOutOfMemory;
+        hipError_t e = hipMalloc(out, bytes ? bytes : 16);
+        if (e == hipSuccess) p[n++] = *out;
+        return e;
+    }
+    void release(void *q)
+    {
+        for (int i = 0; i < n; ++i)
+            if (p[i] == q) p[i] = nullptr;
+    }
+    ~Scratch()
+    {
+        for (int i = 0; i < n; ++i)
+            if (p[i]) (void)hipFree(p[i]);
+    }
+};
+
+#define HIP_TRY(expr)                  \
+    do {                               \
+        hipError_t e_ = (expr);        \
+        if (e_ != hipSuccess) {        \
+            *hip_err = (int)e_;        \
+            (void)hipGetLastError();   \
+            return e_ == hipErrorOutOfMemory ? PCSR_E_OOM : PCSR_E_HIP; \
+        }                              \
+    } while (0)
+
+hipError_t exclusive_scan(const int32_t *in, int32_t *out, int64_t n, Scratch &sc)
+{
+    size_t bytes = 0;
+    hipError_t e = hipcub::DeviceScan::ExclusiveSum(nullptr, bytes, in, out, (int)n);
+    if (e != hipSuccess) return e;
+    void *tmp = nullptr;
+    e = sc.alloc(&tmp, bytes);
+    if (e != hipSuccess) return e;
+    e = hipcub::DeviceScan::ExclusiveSum(tmp, bytes, in, out, (int)n);
+    return e;
+}
+
+} // namespace
+
+int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_rowptr,
+                 const int32_t *d_colidx, const float *d_vals, int32_t V, int32_t S, int32_t SG,
+                 int32_t omega, bool validate, DeviceBuild *out, int *hip_err)
+{
+    if (V != 1 && V != 2) return PCSR_E_UNSUPPORTED;
+    if (omega == 0) omega = 64;
+    Scratch sc;
+    const int64_t P = (n_rows + V - 1) / V;
+
+    // the row pointer must start at 0 and end at nnz
+    int32_t ends[2] = {0, 0};
+    HIP_TRY(hipMemcpy(&ends[0], d_rowptr, sizeof(int32_t), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(&ends[1], d_rowptr + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (ends[0] != 0 || ends[1] != nnz) return PCSR_E_BAD_CSR;
+
+    int *d_flags = nullptr; // [0] bad csr, [1] longest panel, [2] split count; [4..5] nonempty (64 bit)
+    HIP_TRY(sc.alloc((void **)&d_flags, 8 * sizeof(int)));
+    HIP_TRY(hipMemset(d_flags, 0, 8 * sizeof(int)));
+    if (validate && n_rows > 0) {
+        hipLaunchKernelGGL(validate_kernel, dim3(blocks_for(n_rows)), dim3(kThreads), 0, 0, n_rows, n_cols,
+                           nnz, d_rowptr, d_colidx, d_flags);
+        HIP_TRY(hipGetLastError());
+        int bad = 0;
+        HIP_TRY(hipMemcpy(&bad, d_flags, sizeof(int), hipMemcpyDeviceToHost));
+        if (bad) return PCSR_E_BAD_CSR;
+    }
+
+    // ---- vectorised blocking
+    int32_t *prow = nullptr, *pcol = nullptr;
+    float *pval = nullptr;
+    int64_t nnz_v = nnz;
+    HIP_TRY(sc.alloc((void **)&prow, sizeof(int32_t) * (P + 1)));
+    if (V == 1) {
+        HIP_TRY(hipMemcpy(prow, d_rowptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToDevice));
+        HIP_TRY(sc.alloc((void **)&pcol, sizeof(int32_t) * (nnz + 1)));
+        HIP_TRY(sc.alloc((void **)&pval, sizeof(float) * (nnz + 1)));
+        if (nnz) {
+            HIP_TRY(hipMemcpy(pcol, d_colidx, sizeof(int32_t) * nnz, hipMemcpyDeviceToDevice));
+            HIP_TRY(hipMemcpy(pval, d_vals, sizeof(float) * nnz, hipMemcpyDeviceToDevice));
+        }
+    } else {
+        int32_t *cnt = nullptr;
+        HIP_TRY(sc.alloc((void **)&cnt, sizeof(int32_t) * (P + 1)));
+        hipLaunchKernelGGL(count_union_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, n_rows,
+                           d_rowptr, d_colidx, cnt);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(exclusive_scan(cnt, prow, P + 1, sc));
+        int32_t total = 0;
+        HIP_TRY(hipMemcpy(&total, prow + P, sizeof(int32_t), hipMemcpyDeviceToHost));
+        nnz_v = total;
+        HIP_TRY(sc.alloc((void **)&pcol, sizeof(int32_t) * (nnz_v + 1)));
+        HIP_TRY(sc.alloc((void **)&pval, sizeof(float) * (2 * nnz_v + 1)));
+        if (P > 0) {
+            hipLaunchKernelGGL(fill_union_kernel, dim3(blocks_for(P)), dim3(kThreads), 0, 0, P, n_rows,
+                               d_rowptr, d_colidx, d_vals, prow, pcol, pval);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+
+    // ---- Eq. (3) from the panel lengths
+    if (P > 0) {
+        hipLaunchKernelGGL(panel_stats_kernel, dim3(blocks_for(P)), dim3(kThreads), 0, 0, P, prow,
+                           reinterpret_cast<unsigned long long *>(d_flags + 4), d_flags + 1);
+        HIP_TRY(hipGetLastError());
+    }
+    int h_flags[8];
+    HIP_TRY(hipMemcpy(h_flags, d_flags, sizeof(h_flags), hipMemcpyDeviceToHost));
+    unsigned long long nonempty = 0;
+    memcpy(&nonempty, &h_flags[4], sizeof(nonempty));
+    const int64_t longest = h_flags[1];
+    int64_t sg = SG;
+    if (sg <= 0) {
+        sg = (nnz_v == 0 || nonempty == 0)
+                 ? omega
+                 : ((nnz_v + (int64_t)nonempty * omega - 1) / ((int64_t)nonempty * omega)) * omega;
+    }
+    if (sg >= (int64_t(1) << 31)) return PCSR_E_TOO_LARGE;
+
+    out->P = P;
+    out->nnz_v = nnz_v;
+    out->SG = (int32_t)sg;
+    out->n_split = 0;
+    out->trow = nullptr;
+    out->split = nullptr;
+
+    int32_t *final_rowptr = prow;
+    int64_t M = P;
+    if (!S) {
+        out->max_item_len = longest;
+    } else {
+        if (P + nnz_v / sg >= (int64_t(1) << 31) - 2) return PCSR_E_TOO_LARGE;
+        int32_t *items = nullptr, *first = nullptr;
+        HIP_TRY(sc.alloc((void **)&items, sizeof(int32_t) * (P + 1)));
+        HIP_TRY(sc.alloc((void **)&first, sizeof(int32_t) * (P + 1)));
+        hipLaunchKernelGGL(items_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, prow, (int32_t)sg,
+                           items);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(exclusive_scan(items, first, P + 1, sc));
+        int32_t m32 = 0;
+        HIP_TRY(hipMemcpy(&m32, first + P, sizeof(int32_t), hipMemcpyDeviceToHost));
+        M = m32;
+        int32_t *srow = nullptr, *trow = nullptr, *split = nullptr;
+        HIP_TRY(sc.alloc((void **)&srow, sizeof(int32_t) * (M + 1)));
+        HIP_TRY(sc.alloc((void **)&trow, sizeof(int32_t) * (M + 1)));
+        HIP_TRY(sc.alloc((void **)&split, sizeof(int32_t) * (P + 1)));
+        if (P > 0) {
+            hipLaunchKernelGGL(split_fill_kernel, dim3(blocks_for(P)), dim3(kThreads), 0, 0, P, prow, first,
+                               (int32_t)sg, srow, trow, split, d_flags + 2);
+            HIP_TRY(hipGetLastError());
+        } else {
+            HIP_TRY(hipMemset(srow, 0, sizeof(int32_t)));
+        }
+        int n_split = 0;
+        HIP_TRY(hipMemcpy(&n_split, d_flags + 2, sizeof(int), hipMemcpyDeviceToHost));
+        out->n_split = n_split;
+        out->max_item_len = sg < nnz_v ? sg : nnz_v;
+        out->trow = trow;
+        out->split = split;
+        sc.release(trow);
+        sc.release(split);
+        final_rowptr = srow;
+    }
+    out->M = M;
+
+    int32_t *d_xb = nullptr;
+    HIP_TRY(sc.alloc((void **)&d_xb, 9 * sizeof(int32_t)));
+    hipLaunchKernelGGL(xcd_bounds_kernel, dim3(1), dim3(64), 0, 0, (int32_t)M, final_rowptr, d_xb);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpy(out->xcd_bounds, d_xb, 9 * sizeof(int32_t), hipMemcpyDeviceToHost));
+    HIP_TRY(hipDeviceSynchronize());
+
+    out->rowptr = final_rowptr;
+    out->colidx = pcol;
+    out->val = pval;
+    sc.release(final_rowptr);
+    sc.release(pcol);
+    sc.release(pval);
+    return PCSR_OK;
+}
+
+} // namespace pcsr

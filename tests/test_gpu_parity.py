@@ -350,3 +350,59 @@ def test_widths_that_are_not_powers_of_two(K):
     sel = pc.pcsr_select(f, K)
     C = _spmm(g, B, sel, K)
     _check(C, ref, bound, f"K={K} selected")
+
+
+@pytest.mark.parametrize("name", ["poisson", "road", "rmat20", "sbm", "rmat22"])
+@pytest.mark.parametrize("V", [1, 2])
+@pytest.mark.parametrize("S,SG,omega", [(0, 0, 0), (1, 0, 0), (1, 0, 32), (1, 5, 0)])
+@pytest.mark.parametrize("device_csr", [False, True])
+def test_gpu_side_generation_bit_exact(name, V, S, SG, omega, device_csr):
+    """PCSR arrays generated by GPU kernels equal the numpy format reference bit for bit."""
+    g = _graph(name)
+    if device_csr:
+        arrs = [torch.from_numpy(x).cuda() for x in (g.rowptr, g.colidx, g.vals)]
+        flags = 0
+    else:
+        arrs = [g.rowptr, g.colidx, g.vals]
+        flags = pc.PCSR_FLAG_GPU_BUILD
+    h = pc.pcsr_build(g.n_rows, g.n_cols, *arrs, pc.make_params(V=V, S=S, SG=SG, omega=omega, flags=flags))
+    e = pc.pcsr_export(h)
+    r = pf.pcsr_ref(g.n_rows, g.rowptr, g.colidx, g.vals, V, S, SG, omega or 64)
+    for k in ("P", "M", "nnz_v", "V", "SG"):
+        assert e[k] == r[k], k
+    for k in ("rowptr", "colidx", "trow"):
+        assert np.array_equal(e[k], r[k]), k
+    assert np.array_equal(e["val"].view(np.uint32), r["val"].view(np.uint32))
+    # and the handle computes the right product
+    K = 16
+    B, ref, bound = _oracle(name, g, K, synth.WORKLOADS[name]["B"])
+    Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+    pc.pcsr_spmm(h, torch.from_numpy(B).cuda(), Cd, K)
+    torch.cuda.synchronize()
+    _check(Cd.cpu().numpy(), ref, bound, f"gpu build {name} V={V} S={S}")
+    h.close()
+
+
+def test_gpu_side_generation_degenerate_and_bad_input():
+    G = pc.PCSR_FLAG_GPU_BUILD
+    for n in (0, 1, 3):
+        rowptr = np.zeros(n + 1, np.int32)
+        for V in (1, 2):
+            for S in (0, 1):
+                h = pc.pcsr_build(n, 4, rowptr, np.zeros(0, np.int32), np.zeros(0, np.float32),
+                                  pc.make_params(V=V, S=S, flags=G))
+                e = pc.pcsr_export(h)
+                r = pf.pcsr_ref(n, rowptr, np.zeros(0, np.int32), np.zeros(0, np.float32), V, S, 0, 64)
+                assert e["M"] == r["M"] and np.array_equal(e["rowptr"], r["rowptr"])
+                assert np.array_equal(e["trow"], r["trow"])
+                h.close()
+    rp = np.array([0, 2, 3], np.int32)
+    va = np.ones(3, np.float32)
+    for bad_cols in ([1, 0, 2], [1, 1, 2], [0, 3, 2], [0, -1, 2]):
+        with pytest.raises(pc.PcsrError) as ei:
+            pc.pcsr_build(2, 3, rp, np.array(bad_cols, np.int32), va, pc.make_params(flags=G))
+        assert ei.value.code == pc.binding.PCSR_E_BAD_CSR
+    with pytest.raises(pc.PcsrError) as ei:
+        pc.pcsr_build(2, 3, np.array([0, 3, 2], np.int32), np.array([0, 1, 2], np.int32), va,
+                      pc.make_params(flags=G))
+    assert ei.value.code == pc.binding.PCSR_E_BAD_CSR
