@@ -25,7 +25,10 @@ HBM_PEAK_GBS = 8000.0
 # each scaled by what the counter reads for a plain copy kernel of known size); the
 # summaries with the commands are under profiles/.  Keyed by (workload, K).
 PROFILED_TRAFFIC = {
-    ("road-full", 128): 2_121_501_891,   # profiles/spmm_road_K128.md
+    ("road-full", 128): 2_121_501_891,      # profiles/spmm_road_K128.md
+    ("sbm-full", 256): 1_867_418_528,       # profiles/spmm_sbm_K256.md
+    ("rmat20-full", 64): 2_996_129_152,     # profiles/spmm_rmat20_K64.md
+    ("rmat22-full", 64): 29_434_107_301,    # profiles/spmm_rmat22_K64.md
 }
 
 
@@ -53,6 +56,7 @@ def main() -> int:
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--items-per-group", type=int, default=0)
     ap.add_argument("--col-window", type=int, default=-1, help="-1 = library selector")
+    ap.add_argument("--gpu-build", action="store_true", help="generate the PCSR arrays with GPU kernels")
     ap.add_argument("--reorder", action="store_true",
                     help="apply the library's locality reordering first (A' = P A P^T, B' = P B); the timed "
                          "SpMM runs on the relabelled problem and its result is checked as C = P^T C'")
@@ -109,7 +113,8 @@ def main() -> int:
         rep=args.rep or sel.rep, waves_per_wg=args.waves or sel.waves_per_wg,
         items_per_group=args.items_per_group or sel.items_per_group,
         col_window=sel.col_window if args.col_window < 0 else args.col_window,
-        flags=pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
+        flags=(pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
+        | (pc.PCSR_FLAG_GPU_BUILD if args.gpu_build else 0))
     t0 = time.time()
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, params)
     build_ms = (time.time() - t0) * 1e3

@@ -16,6 +16,18 @@
 // logarithmic-ish on rows with 1e5 nonzeros.
 #include "pcsr_kernels.h"
 
+// registers of B data a lane keeps in flight per gather step
+#ifndef PCSR_INFLIGHT
+#define PCSR_INFLIGHT 16
+#endif
+// balanced (power-law) inputs are bound by the latency of scattered gathers: go deeper
+#ifndef PCSR_INFLIGHT_SPLIT
+#define PCSR_INFLIGHT_SPLIT 32
+#endif
+#ifndef PCSR_MAXSTEP
+#define PCSR_MAXSTEP 8
+#endif
+
 namespace pcsr {
 namespace {
 
@@ -99,8 +111,8 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
 {
     constexpr int G = 64 / LPR;
     // vectors gathered per inner step: about 16 registers of B data in flight
-    constexpr int U0 = 16 / (REP * VEC);
-    constexpr int U = U0 < 1 ? 1 : (U0 > 8 ? 8 : (U0 > LPR ? LPR : U0));
+    constexpr int U0 = (S ? PCSR_INFLIGHT_SPLIT : PCSR_INFLIGHT) / (REP * VEC);
+    constexpr int U = U0 < 1 ? 1 : (U0 > PCSR_MAXSTEP ? PCSR_MAXSTEP : (U0 > LPR ? LPR : U0));
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int waves = blockDim.x >> 6;
@@ -258,7 +270,7 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
 {
     static_assert(IPG < LPR, "item boundaries are broadcast from the group's own lanes");
     constexpr int G = 64 / LPR;
-    constexpr int U0 = 16 / (REP * VEC);
+    constexpr int U0 = PCSR_INFLIGHT / (REP * VEC);
     constexpr int U = U0 < 1 ? 1 : (U0 > 8 ? 8 : (U0 > LPR ? LPR : U0));
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -396,7 +408,7 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
     constexpr int G = 64 / LPR;
     constexpr int TW = LPR * VEC * REP; // columns per slice
     constexpr int LW = TW + 4;          // floats per staged row, padded so rows start on different banks
-    constexpr int U0 = 16 / (REP * VEC);
+    constexpr int U0 = PCSR_INFLIGHT / (REP * VEC);
     constexpr int U = U0 < 1 ? 1 : (U0 > 8 ? 8 : (U0 > LPR ? LPR : U0));
     const int tid = threadIdx.x;
     const int lane = tid & 63;
