@@ -118,7 +118,8 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
  *      call does not wait for it and allocates nothing.
  * With S = 0 the result is bit-reproducible run to run.  With S = 1 rows that were
  * split are accumulated with fp32 atomics, so their summation order may vary.
- * Errors: INVALID_ARG, UNSUPPORTED, HIP.
+ * Errors: INVALID_ARG (null or misaligned or overlapping B / C, handle built on another
+ * device than the current one), UNSUPPORTED, HIP.
  */
 int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream);
 

@@ -341,6 +341,17 @@ int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream
     if ((reinterpret_cast<uintptr_t>(B) % align) || (reinterpret_cast<uintptr_t>(C) % align))
         return PCSR_E_INVALID_ARG;
     if (h->host.n_rows == 0) return PCSR_OK;
+    {
+        // B and C may not overlap: the kernel reads B while other workgroups write C
+        const uintptr_t b0 = reinterpret_cast<uintptr_t>(B), c0 = reinterpret_cast<uintptr_t>(C);
+        const uintptr_t b1 = b0 + (uintptr_t)h->host.n_cols * (uintptr_t)K * 4u;
+        const uintptr_t c1 = c0 + (uintptr_t)h->host.n_rows * (uintptr_t)K * 4u;
+        if (b0 < c1 && c0 < b1 && h->host.n_cols > 0) return PCSR_E_INVALID_ARG;
+        // the handle's arrays live on the device that was current at pcsr_build
+        int dev = -1;
+        if (!hip_ok(hipGetDevice(&dev))) return PCSR_E_HIP;
+        if (dev != h->device) return PCSR_E_INVALID_ARG;
+    }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (h->host.S && h->n_split > 0) {
@@ -484,8 +495,11 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.
     const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
+    // Balanced power-law inputs do best with four items per wavefront (16 lanes each)
+    // whatever K is: repeats, then grid.y slices, cover the rest of the row.
+    const int lpr_cap = p.S ? 16 : 64;
     int lpr = 4;
-    while (lpr * vec < K && lpr < 64) lpr <<= 1;
+    while (lpr * vec < K && lpr < lpr_cap) lpr <<= 1;
     int rep = 1;
     while (lpr * vec * rep < K && rep < 4) rep <<= 1;
     if (!p.S && p.V == 1 && d_hat < 8.0 && lpr >= 32 && rep == 1) {
@@ -495,9 +509,9 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     p.lanes_per_row = lpr;
     p.vec = vec;
     p.rep = rep;
-    // Workgroup size: single-wave groups retire independently, which suits items of very
-    // different lengths; long uniform rows like full workgroups; short rows sit between.
-    p.waves_per_wg = p.S ? 1 : (d_hat >= 16.0 ? 8 : 2);
+    // Workgroup size: long uniform rows like full workgroups, short rows and items of
+    // very different lengths smaller ones.
+    p.waves_per_wg = p.S ? 4 : (d_hat >= 16.0 ? 8 : 2);
     p.items_per_group = 1;
     p.col_window = 0;
     (void)n;

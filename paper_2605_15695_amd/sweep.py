@@ -243,14 +243,25 @@ def main(argv=None) -> int:
         med, mn = time_launches(lambda: pc.pcsr_spmm(hsel, Bd, Cd, K, stream), stream, torch,
                                 args.warmup, args.reps)
         dev = float((Cd - Cref).abs().max().item()) / scale if Cref is not None else None
+        # time the sweep's best tuple again, back to back with the pick, so that the ratio
+        # compares two measurements taken under the same conditions
+        best_again = None
+        if best[1]:
+            b = best[1]
+            hb = handles[(b["V"], b["S"], b["SG"], b["col_window"])]
+            pc.pcsr_set_kernel_params(hb, b["lanes_per_row"], b["vec"], b["rep"], b["waves_per_wg"],
+                                      b["items_per_group"], 0 if b["xcd_remap"] else pc.PCSR_FLAG_NO_XCD_REMAP)
+            best_again, _ = time_launches(lambda: pc.pcsr_spmm(hb, Bd, Cd, K, stream), stream, torch,
+                                          args.warmup, args.reps)
         selrec = dict(base, kind="selected", V=sel.V, S=sel.S, SG=sel.SG, **qs, ms_median=med, ms_min=mn,
                       gflops=flops / med / 1e6, roofline_frac=bytes_min / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                      max_rel_dev=dev, vs_sweep_best=(best[0] / med) if best[1] else None)
+                      max_rel_dev=dev, best_retimed_ms=best_again,
+                      vs_sweep_best=(best_again / med) if best_again else None)
         emit(selrec)
         hsel.close()
         print(f"[sweep] K={K} SELECTED V={sel.V} S={sel.S} SG={sel.SG} lpr={qs['lanes_per_row']} vec={qs['vec']} "
               f"rep={qs['rep']} gy={qs['grid_y']} waves={qs['waves_per_wg']}: {med:.4f} ms "
-              f"({100 * best[0] / med:.1f}% of sweep best)", flush=True)
+              f"({100 * (best_again or best[0]) / med:.1f}% of the sweep's best tuple re-timed)", flush=True)
         summary = dict(base, kind="summary", selected=selrec, pcsr_best=best[1], hipsparse_best=hs_best[1],
                        speedup_vs_hipsparse=(hs_best[0] / best[0]) if hs_best[1] and best[1] else None)
         emit(summary)

@@ -312,13 +312,17 @@ def test_long_row_accumulation_stays_in_tolerance():
             _check(C, ref, bound, f"long row S={S} {kern}")
 
 
-def test_full_size_road_sampled_rows():
-    """The bench workload at full size in the bench's launch configuration; the oracle
-    recomputes a sample of rows one by one."""
-    g = synth.workload("road", "full")
-    K = 128
-    B = synth.dense_operand(g.n_cols, K, "normal", 2)
-    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params())
+@pytest.mark.parametrize("name,K", [("road", 128), ("rmat20", 64), ("sbm", 256), ("sbm_shuffled", 256),
+                                    ("rmat22", 32)])
+def test_full_size_sampled_rows(name, K):
+    """Every benchmark workload at full size in the launch configuration bench.py times
+    (the library's own pick); the oracle recomputes a sample of rows one by one, the
+    longest rows and some empty ones included."""
+    g = synth.workload(name, "full")
+    B = synth.dense_operand(g.n_cols, K, synth.WORKLOADS[name]["B"], 2)
+    sel = pc.pcsr_select(pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx), K)
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, sel)
+    print(f"case full {name} K={K} V={sel.V} S={sel.S} SG={sel.SG} {pc.pcsr_query_launch(h, K)}", flush=True)
     Bd = torch.from_numpy(B).cuda()
     Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
     pc.pcsr_spmm(h, Bd, Cd, K)
@@ -329,7 +333,7 @@ def test_full_size_road_sampled_rows():
                                      np.argsort(deg)[-50:], np.nonzero(deg == 0)[0][:50]]))
     ref, bound = oracle.spmm_rows(g.rowptr, g.colidx, g.vals, B, rows)
     got = Cd[torch.from_numpy(rows).cuda()].cpu().numpy()
-    _check(got, ref, bound, "road full sampled")
+    _check(got, ref, bound, f"{name} full sampled")
     # property that holds at any size: nothing left unwritten
     assert not torch.isnan(Cd).any().item()
     h.close()
@@ -406,3 +410,39 @@ def test_gpu_side_generation_degenerate_and_bad_input():
         pc.pcsr_build(2, 3, np.array([0, 3, 2], np.int32), np.array([0, 1, 2], np.int32), va,
                       pc.make_params(flags=G))
     assert ei.value.code == pc.binding.PCSR_E_BAD_CSR
+
+
+def test_spmm_argument_checks():
+    g = _graph("poisson")
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params())
+    K = 16
+    buf = torch.zeros((g.n_rows + g.n_cols) * K + 8, dtype=torch.float32, device="cuda")
+    lib = pc.binding._lib()
+    base = buf.data_ptr()
+    # overlapping B and C
+    assert lib.pcsr_spmm(h.raw, base, base + 4 * K, K, None) == pc.binding.PCSR_E_INVALID_ARG
+    # misaligned for float4 loads
+    assert lib.pcsr_spmm(h.raw, base + 4, base + 4 * (g.n_cols * K + 4), K, None) == pc.binding.PCSR_E_INVALID_ARG
+    assert lib.pcsr_spmm(h.raw, base, base + 4 * g.n_cols * K, 0, None) == pc.binding.PCSR_E_UNSUPPORTED
+    assert lib.pcsr_spmm(h.raw, None, base, K, None) == pc.binding.PCSR_E_INVALID_ARG
+    # adjacent but disjoint is fine
+    assert lib.pcsr_spmm(h.raw, base, base + 4 * g.n_cols * K, K, None) == 0
+    torch.cuda.synchronize()
+    h.close()
+
+
+@pytest.mark.parametrize("name", ["sbm_shuffled", "rmat20"])
+def test_reordered_problem_gives_the_same_product(name):
+    """A' = P A P^T, B' = P B  =>  C' = P C: the library's reorder + relabel against the
+    oracle on the original problem."""
+    g = _graph(name)
+    K = 32
+    B, ref, bound = _oracle(name, g, K, "normal")
+    perm, _ = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
+    rp, ci, va = pc.pcsr_permute_csr(g.n_rows, g.rowptr, g.colidx, g.vals, perm)
+    g2 = synth.Graph(name + "_r", g.n_rows, g.n_cols, rp, ci, va)
+    B2 = np.empty_like(B)
+    B2[perm] = B
+    sel = pc.pcsr_select(pc.pcsr_features(g2.n_rows, g2.n_cols, rp, ci), K)
+    C2 = _spmm(g2, B2, sel, K)
+    _check(C2[perm], ref, bound, f"reordered {name}")
