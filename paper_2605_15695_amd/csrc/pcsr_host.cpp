@@ -307,11 +307,12 @@ int features_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *ro
     // V = 2 panel lengths
     const int64_t P2 = ceildiv(n_rows, 2);
     std::vector<int32_t> len2(P2);
+    parallel_for(P2, 1 << 13, [&](int64_t lo, int64_t hi) { // the only O(nnz) pass
+        for (int64_t p = lo; p < hi; ++p) len2[p] = (int32_t)union_count(rowptr, colidx, 2 * p, n_rows);
+    });
     for (int64_t p = 0; p < P2; ++p) {
-        int64_t l = union_count(rowptr, colidx, 2 * p, n_rows);
-        len2[p] = (int32_t)l;
-        nnz2 += l;
-        nonempty2 += (l > 0);
+        nnz2 += len2[p];
+        nonempty2 += (len2[p] > 0);
     }
     const int64_t sg1 = eq3_sg(nnz, n_hat, omega), sg2 = eq3_sg(nnz2, nonempty2, omega);
     int64_t M1 = 0, M2 = 0;
