@@ -63,6 +63,9 @@ def main() -> int:
     ap.add_argument("--no-xcd-remap", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--graph-batch", type=int, default=-1,
+                    help="also capture this many SpMMs in one HIP graph and report the replay time per SpMM "
+                         "beside the launch floor (-1 = 64 when one launch takes under 50 us, else off)")
     ap.add_argument("--no-hipsparse", action="store_true", help="skip the hipSPARSE SpMM comparison leg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel (reads 1 GiB, writes 1 GiB) so a "
@@ -180,6 +183,40 @@ def main() -> int:
         "setup": {"generate_s": gen_s, "features_select_ms": feat_ms, "pcsr_build_ms": build_ms,
                   "reorder_ms": reorder_ms},
     }
+
+    gb = args.graph_batch if args.graph_batch >= 0 else (64 if kern_ms < 0.05 else 0)
+    if gb > 0:
+        # launch-bound regime: N SpMMs replayed from one captured graph, and the same graph
+        # shape filled with a one-element kernel as the floor of what a launch costs
+        side = torch.cuda.Stream()
+        tiny = torch.zeros(64, device="cuda")
+
+        def captured(fn):
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                fn(side)
+            side.synchronize()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                for _ in range(gb):
+                    fn(torch.cuda.current_stream())
+            for _ in range(3):
+                gr.replay()
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(20):
+                t0 = time.perf_counter()
+                gr.replay()
+                torch.cuda.synchronize()
+                ts.append((time.perf_counter() - t0) * 1e6 / gb)
+            return statistics.median(ts)
+
+        us_spmm = captured(lambda st: pc.pcsr_spmm(h, Bd, Cd, K, st))
+        us_floor = captured(lambda st: tiny.add_(1.0))
+        out["launch_bound"] = {"graph_batch": gb, "us_per_spmm_in_graph": us_spmm,
+                               "us_per_empty_kernel_in_graph": us_floor,
+                               "us_per_spmm_eager_events": kern_ms * 1e3,
+                               "us_per_step_eager_wall": ms_per_step * 1e3}
 
     if not args.no_hipsparse:
         # vendor baseline on the same arrays (best of its CSR algorithms), outside the timed region

@@ -446,3 +446,34 @@ def test_reordered_problem_gives_the_same_product(name):
     sel = pc.pcsr_select(pc.pcsr_features(g2.n_rows, g2.n_cols, rp, ci), K)
     C2 = _spmm(g2, B2, sel, K)
     _check(C2[perm], ref, bound, f"reordered {name}")
+
+
+@pytest.mark.parametrize("V,S", [(1, 0), (2, 1)])
+def test_spmm_can_be_captured_in_a_hip_graph(V, S):
+    """pcsr_spmm allocates nothing and only launches kernels, so a launch-bound loop of
+    SpMMs can be captured once and replayed; every replay must equal the eager result."""
+    g = _graph("poisson")
+    K = 32
+    B, ref, bound = _oracle("poisson", g, K, "uniform")
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=S, SG=4 if S else 0))
+    Bd = torch.from_numpy(B).cuda()
+    Cd = torch.zeros((g.n_rows, K), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pc.pcsr_spmm(h, Bd, Cd, K, side)          # warm-up outside the capture
+    side.synchronize()
+    eager = Cd.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(4):
+            pc.pcsr_spmm(h, Bd, Cd, K, torch.cuda.current_stream())
+    for replay in range(3):
+        Cd.fill_(float("nan"))                     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        if S == 0:
+            assert torch.equal(Cd, eager), f"replay {replay}"
+        _check(Cd.cpu().numpy(), ref, bound, f"graph replay {replay} V={V} S={S}")
+    h.close()
