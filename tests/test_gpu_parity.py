@@ -477,3 +477,38 @@ def test_spmm_can_be_captured_in_a_hip_graph(V, S):
             assert torch.equal(Cd, eager), f"replay {replay}"
         _check(Cd.cpu().numpy(), ref, bound, f"graph replay {replay} V={V} S={S}")
     h.close()
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 6, 1000, 2048])
+def test_extreme_widths(K):
+    g = _graph("sbm")
+    g = synth.Graph("sbm_head", 2000, g.n_cols, g.rowptr[:2001].copy(), g.colidx[:g.rowptr[2000]],
+                    g.vals[:g.rowptr[2000]])
+    B = synth.dense_operand(g.n_cols, K, "uniform", K)
+    ref, bound = oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+    for V, S in [(1, 0), (2, 1)]:
+        C = _spmm(g, B, pc.make_params(V=V, S=S, SG=16 if S else 0), K)
+        _check(C, ref, bound, f"K={K} V={V} S={S}")
+
+
+def test_two_handles_on_two_streams_concurrently():
+    g1, g2 = _graph("rmat20"), _graph("road")
+    K = 64
+    B1, ref1, bound1 = _oracle("rmat20", g1, K, "normal")
+    B2, ref2, bound2 = _oracle("road", g2, K, "normal")
+    h1 = pc.pcsr_build(g1.n_rows, g1.n_cols, g1.rowptr, g1.colidx, g1.vals, pc.make_params(S=1, SG=32))
+    h2 = pc.pcsr_build(g2.n_rows, g2.n_cols, g2.rowptr, g2.colidx, g2.vals, pc.make_params(V=2))
+    B1d, B2d = torch.from_numpy(B1).cuda(), torch.from_numpy(B2).cuda()
+    C1d = torch.empty((g1.n_rows, K), dtype=torch.float32, device="cuda")
+    C2d = torch.empty((g2.n_rows, K), dtype=torch.float32, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(10):
+        pc.pcsr_spmm(h1, B1d, C1d, K, s1)
+        pc.pcsr_spmm(h2, B2d, C2d, K, s2)
+    s1.synchronize()
+    s2.synchronize()
+    _check(C1d.cpu().numpy(), ref1, bound1, "stream 1")
+    _check(C2d.cpu().numpy(), ref2, bound2, "stream 2")
+    h1.close()
+    h2.close()
