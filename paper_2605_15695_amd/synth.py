@@ -250,7 +250,37 @@ def workload(name: str, size: str = "full") -> Graph:
             return rmat(22, 16, permute=False, symmetric=True, min_dmax=100_001,
                         seed=BASE_SEED + 5)
         return rmat(14, 16, permute=False, symmetric=True, seed=BASE_SEED + 5)
+    if name in EXTRA:
+        return EXTRA[name]()
     raise ValueError(name)
+
+
+# Further inputs, used only to check the configuration rule on shapes it was not fitted to
+# (Section 6.1 stresses the diversity of the evaluated matrices): other sizes, degrees and
+# degree skews of the same four generator families.  They have one size.
+EXTRA = {
+    "x_poisson_d8": lambda: poisson_like(400_000, 8.0, BASE_SEED + 11),
+    "x_poisson_d32": lambda: poisson_like(200_000, 32.0, BASE_SEED + 12),
+    "x_poisson_d96": lambda: poisson_like(60_000, 96.0, BASE_SEED + 13),
+    "x_road_small": lambda: road_grid(700, 500, seed=BASE_SEED + 14),
+    "x_road_dense": lambda: road_grid(1200, 800, mean_draw=5.0, seed=BASE_SEED + 15),
+    "x_rmat18": lambda: rmat(18, 16, permute=True, symmetric=True, seed=BASE_SEED + 16),
+    "x_rmat19_ef8": lambda: rmat(19, 8, permute=False, symmetric=False, seed=BASE_SEED + 17),
+    "x_rmat17_ef64": lambda: rmat(17, 64, permute=True, symmetric=False, seed=BASE_SEED + 18),
+    "x_sbm_small_blocks": lambda: sbm(200_000, 4000, mean_deg=20.0, seed=BASE_SEED + 19),
+    "x_sbm_big_blocks": lambda: sbm(120_000, 24, mean_deg=80.0, p_intra=0.7, seed=BASE_SEED + 20),
+}
+
+
+def poisson_like(n: int, mean_deg: float, seed: int) -> Graph:
+    """Poisson(mean_deg) uniformly random columns per row (duplicates dropped), vectorised for
+    large n; 1/deg values."""
+    rng = _rng(seed)
+    deg = rng.poisson(mean_deg, n)
+    src = np.repeat(np.arange(n, dtype=np.int64), deg)
+    dst = rng.integers(0, n, src.shape[0])
+    rowptr, colidx = csr_from_edges(n, n, src, dst)
+    return Graph(f"poisson_like_{n}_{mean_deg:g}", n, n, rowptr, colidx, values_inv_row_degree(rowptr))
 
 
 WORKLOADS = {
@@ -261,3 +291,4 @@ WORKLOADS = {
     "sbm_shuffled": dict(B="uniform", K=[256]),
     "rmat22": dict(B="normal", K=[16, 32, 64, 128, 256, 512]),
 }
+WORKLOADS.update({name: dict(B="normal", K=[32, 128]) for name in EXTRA})
