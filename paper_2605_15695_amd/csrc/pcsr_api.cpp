@@ -102,8 +102,10 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
             const int fit = (128 * 1024 / 4 / h->host.win_cols - 4) / vec;
             if (need > fit) need = fit;
         }
+        // balanced (power-law) handles: four items per wavefront, as pcsr_select picks
+        const int cap = h->host.S ? 16 : 64;
         lpr = 4;
-        while (lpr < need && lpr < 64) lpr <<= 1;
+        while (lpr < need && lpr < cap) lpr <<= 1;
     }
     int rep = h->rep;
     if (!rep) {
@@ -490,7 +492,7 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     p.omega = 64;
     // Vector size 2 (Section 3.1) when adjacent rows share columns (low padding), and for
     // very short rows, where pairing rows doubles the gathers a lane group keeps in flight.
-    p.V = (!p.S && (d_hat < 6.0 || (pr2 < 0.30 && d_hat >= 4.0))) ? 2 : 1;
+    p.V = (!p.S && (d_hat < 6.0 || (d_hat < 12.0 && pr2 < 0.45) || pr2 < 0.30)) ? 2 : 1;
 
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.
