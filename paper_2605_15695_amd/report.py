@@ -3,7 +3,7 @@ table: per workload and K the best PCSR tuple, its time, GFLOP/s (2*nnz*K), frac
 the HBM minimum-traffic roofline, cache-level gather rate, the library's own pick and
 hipSPARSE's best algorithm, then the geometric-mean speed-up over hipSPARSE.
 
-    python -m paper_2605_15695_amd.report gpurun_out/sweep_*.jsonl > profiles/sweep_summary.md
+    python -m paper_2605_15695_amd.report sweeps/*.jsonl > sweep_summary.md
 """
 from __future__ import annotations
 

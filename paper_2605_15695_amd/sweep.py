@@ -9,7 +9,7 @@ Outputs of all tuples are compared on the GPU with the first tuple's output (max
 |difference| relative to max |C|) as a consistency diagnostic; parity against the
 CPU oracle is the job of the tests and of bench.py.
 
-    python -m paper_2605_15695_amd.sweep --workload rmat20 --K 64 --out gpurun_out/sweep_rmat20.jsonl
+    python -m paper_2605_15695_amd.sweep --workload rmat20 --K 64 --out sweeps/rmat20.jsonl
 """
 from __future__ import annotations
 
