@@ -490,9 +490,12 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     p.S = (cv > 1.5 && d_max > 256.0) ? 1 : 0;
     p.SG = p.S ? (nnz >= 64.0 * 1048576.0 ? 1024 : 256) : 0;
     p.omega = 64;
-    // Vector size 2 (Section 3.1) when adjacent rows share columns (low padding), and for
-    // very short rows, where pairing rows doubles the gathers a lane group keeps in flight.
-    p.V = (!p.S && (d_hat < 6.0 || (d_hat < 12.0 && pr2 < 0.45) || pr2 < 0.30)) ? 2 : 1;
+    // Vector size 2 (Section 3.1) when adjacent rows share columns, and for short rows, where
+    // pairing rows doubles the gathers a lane group keeps in flight.  The paper's A6000 data
+    // puts the break-even near 30 % padding; on MI355X clique-like inputs win at 11 %
+    // padding (1.23x at K=128) and lose at 27 %, because adjacent rows of one wavefront
+    // already share their B lines in L1.
+    p.V = (!p.S && (d_hat < 6.0 || (d_hat < 12.0 && pr2 < 0.45) || pr2 < 0.20)) ? 2 : 1;
 
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.

@@ -269,7 +269,33 @@ EXTRA = {
     "x_rmat17_ef64": lambda: rmat(17, 64, permute=True, symmetric=False, seed=BASE_SEED + 18),
     "x_sbm_small_blocks": lambda: sbm(200_000, 4000, mean_deg=20.0, seed=BASE_SEED + 19),
     "x_sbm_big_blocks": lambda: sbm(120_000, 24, mean_deg=80.0, p_intra=0.7, seed=BASE_SEED + 20),
+    "x_cliques": lambda: cliques(300_000, 24.0, 0.1, BASE_SEED + 21),
+    "x_cliques_noisy": lambda: cliques(300_000, 24.0, 0.5, BASE_SEED + 22),
 }
+
+
+def cliques(n: int, mean_size: float, noise: float, seed: int) -> Graph:
+    """Co-authorship-like graph: consecutive ids are cut into cliques of 4 + Poisson(mean_size-4)
+    nodes (every member linked to every member, itself included), and each row gets
+    Poisson(noise * clique size) extra uniformly random columns.  Adjacent rows share almost all
+    their columns, the low-padding regime of the paper's Table 1.  1/deg values."""
+    rng = _rng(seed)
+    sizes = 4 + rng.poisson(max(mean_size - 4.0, 0.0), int(n / mean_size * 1.2) + 8)
+    ends = np.cumsum(sizes)
+    k = int(np.searchsorted(ends, n))
+    sizes = sizes[:k + 1].copy()
+    sizes[k] -= ends[k] - n
+    sizes = sizes[sizes > 0]
+    start = np.repeat(np.cumsum(sizes) - sizes, sizes)      # first id of each node's clique
+    size = np.repeat(sizes, sizes)
+    src = np.repeat(np.arange(n, dtype=np.int64), size)
+    within = np.arange(src.shape[0], dtype=np.int64) - np.repeat(np.cumsum(size) - size, size)
+    dst = np.repeat(start, size) + within
+    extra = rng.poisson(noise * size)
+    src2 = np.repeat(np.arange(n, dtype=np.int64), extra)
+    dst2 = rng.integers(0, n, src2.shape[0])
+    rowptr, colidx = csr_from_edges(n, n, np.concatenate([src, src2]), np.concatenate([dst, dst2]))
+    return Graph(f"cliques_{n}_{noise:g}", n, n, rowptr, colidx, values_inv_row_degree(rowptr))
 
 
 def poisson_like(n: int, mean_deg: float, seed: int) -> Graph:
