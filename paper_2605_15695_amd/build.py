@@ -39,7 +39,9 @@ def build(verbose: bool = False) -> pathlib.Path:
     subprocess.run(cmd, check=True)
     # vendor baseline used by the benchmarks (links hipSPARSE; not part of libpcsr.so)
     base = _compile("baseline_hipsparse.cpp")
-    subprocess.run([HIPCC, "-shared", "-fPIC", str(base), "-o", str(BASELINE_LIB),
+    probe = _compile("probe_gather.hip")
+    subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", str(base), str(probe), "-o",
+                    str(BASELINE_LIB),
                     "-L/opt/rocm/lib", "-lhipsparse", "-Wl,-rpath,/opt/rocm/lib"], check=True)
     if verbose:
         print(LIB, BASELINE_LIB)
