@@ -15,7 +15,13 @@ import sys
 
 
 def main(argv=None) -> int:
+    import argparse
+
     import torch
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--footprints-mb", type=float, nargs="*", default=[16, 256, 1024, 8192])
+    args = ap.parse_args(argv)
 
     if not torch.cuda.is_available():
         print("gather_probe: no GPU visible", file=sys.stderr)
@@ -28,9 +34,9 @@ def main(argv=None) -> int:
     out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
     n_idx = 1 << 25
     results = []
-    for footprint_mb in (16, 256, 1024, 8192):
+    for footprint_mb in args.footprints_mb:
         for row_floats in (16, 32, 64, 128, 256):
-            n_rows = footprint_mb * (1 << 20) // (row_floats * 4)
+            n_rows = int(footprint_mb * (1 << 20)) // (row_floats * 4)
             B = torch.ones((n_rows, row_floats), dtype=torch.float32, device="cuda")
             idx = torch.randint(0, n_rows, (n_idx,), dtype=torch.int32, device="cuda")
 
