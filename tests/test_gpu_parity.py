@@ -512,3 +512,51 @@ def test_two_handles_on_two_streams_concurrently():
     _check(C2d.cpu().numpy(), ref2, bound2, "stream 2")
     h1.close()
     h2.close()
+
+
+def test_seeded_random_configurations():
+    """120 seeded random (matrix, K, format, launch shape) combinations against the oracle."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    for case in range(120):
+        n_rows = int(rng.integers(1, 400))
+        n_cols = int(rng.integers(1, 600))
+        density = float(rng.choice([0.0, 0.01, 0.05, 0.3, 0.9]))
+        rp, ci, va, _ = random_csr(rng, n_rows, n_cols, density,
+                                   full_rows=(int(rng.integers(0, n_rows)),) if rng.random() < 0.3 else ())
+        K = int(rng.choice([1, 2, 4, 7, 8, 12, 16, 24, 32, 48, 64, 100, 128, 132, 256]))
+        V = int(rng.choice([1, 2]))
+        S = int(rng.choice([0, 1]))
+        SG = int(rng.choice([0, 1, 3, 64])) if S else 0
+        cw = int(rng.choice([0, 0, 256, 512])) if not S else 0
+        vec = int(rng.choice([v for v in (1, 2, 4) if K % v == 0]))
+        lpr = int(rng.choice([4, 8, 16, 32, 64]))
+        rep = int(rng.choice([1, 2, 4]))
+        waves = int(rng.choice([1, 2, 4, 8]))
+        ipg = int(rng.choice([1, 1, 2, 4])) if not S and not cw else 1
+        flags = pc.PCSR_FLAG_NO_XCD_REMAP if rng.random() < 0.3 else 0
+        if rng.random() < 0.3 and not cw:
+            flags |= pc.PCSR_FLAG_GPU_BUILD
+        what = (f"case {case}: {n_rows}x{n_cols} d={density} K={K} V={V} S={S} SG={SG} cw={cw} "
+                f"lpr={lpr} vec={vec} rep={rep} waves={waves} ipg={ipg} flags={flags}")
+        print(what, flush=True)
+        g = synth.Graph("rnd", n_rows, n_cols, rp, ci, va)
+        h = pc.pcsr_build(n_rows, n_cols, rp, ci, va, pc.make_params(V=V, S=S, SG=SG, col_window=cw, flags=flags))
+        pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, ipg, flags & pc.PCSR_FLAG_NO_XCD_REMAP)
+        try:
+            q = pc.pcsr_query_launch(h, K)
+        except pc.PcsrError:
+            h.close()
+            continue                              # combination the library documents as unsupported
+        if q["grid_y"] > 64:
+            h.close()
+            continue
+        B = synth.dense_operand(n_cols, K, "normal", case)
+        ref, bound = oracle.spmm(rp, ci, va, B)
+        Cd = torch.full((n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+        pc.pcsr_spmm(h, torch.from_numpy(B).cuda(), Cd, K)
+        torch.cuda.synchronize()
+        _check(Cd.cpu().numpy(), ref, bound, what)
+        h.close()
+        done += 1
+    assert done >= 80
