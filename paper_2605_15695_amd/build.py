@@ -40,7 +40,8 @@ def build(verbose: bool = False) -> pathlib.Path:
     # vendor baseline used by the benchmarks (links hipSPARSE; not part of libpcsr.so)
     base = _compile("baseline_hipsparse.cpp")
     probe = _compile("probe_gather.hip")
-    subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", str(base), str(probe), "-o",
+    alg1 = _compile("baseline_alg1.hip")
+    subprocess.run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", str(base), str(probe), str(alg1), "-o",
                     str(BASELINE_LIB),
                     "-L/opt/rocm/lib", "-lhipsparse", "-Wl,-rpath,/opt/rocm/lib"], check=True)
     if verbose:

@@ -20,8 +20,8 @@ def main(argv=None) -> int:
             recs += [json.loads(line) for line in f if line.strip()]
     keys = sorted({(r["workload"], r["K"]) for r in recs if r.get("kind") == "pcsr"})
     print("| workload | K | n | nnz | best tuple (V,S,SG / lanes,vec,rep,waves,items) | ms | GFLOP/s | roofline frac "
-          "| gather TB/s | selected ms (% of best) | hipSPARSE best ms | speed-up |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
+          "| gather TB/s | selected ms (% of best) | hipSPARSE best ms | speed-up | Alg. 1 ms |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     ratios, sel_ratios, at_half = [], [], 0
     for w, K in keys:
         rs = [r for r in recs if r.get("kind") == "pcsr" and r["workload"] == w and r["K"] == K]
@@ -30,6 +30,8 @@ def main(argv=None) -> int:
               and "ms_median" in r]
         sel = [r for r in recs if r.get("kind") == "selected" and r["workload"] == w and r["K"] == K]
         h = min(hs, key=lambda r: r["ms_median"]) if hs else None
+        a1 = [r["ms_median"] for r in recs if r.get("kind") == "alg1" and r["workload"] == w and r["K"] == K]
+        a1_txt = f"{min(a1):.4f}" if a1 else "-"
         s = min(sel, key=lambda r: r["ms_median"]) if sel else None
         tup = (f'{b["V"]},{b["S"]},{b["SG"]} / {b["lanes_per_row"]},{b["vec"]},{b["rep"]},'
                f'{b["waves_per_wg"]},{b.get("items_per_group", 1)}')
@@ -45,7 +47,7 @@ def main(argv=None) -> int:
             sel_ratios.append(sref / s["ms_median"])
         at_half += b["roofline_frac"] >= 0.5
         print(f'| {w} | {K} | {b["n"]} | {b["nnz"]} | {tup} | {b["ms_median"]:.4f} | {b["gflops"]:.0f} | '
-              f'{b["roofline_frac"]:.3f} | {gather:.2f} | {sel_txt} | {hs_txt} | {sp:.2f}x |')
+              f'{b["roofline_frac"]:.3f} | {gather:.2f} | {sel_txt} | {hs_txt} | {sp:.2f}x | {a1_txt} |')
     if ratios:
         gm = math.exp(sum(map(math.log, ratios)) / len(ratios))
         print(f"\nGeometric mean of hipSPARSE best / PCSR best over {len(ratios)} inputs: **{gm:.2f}x**; "

@@ -82,6 +82,7 @@ def _baseline_lib():
     lib.hsp_spmm_destroy.argtypes = [vp]
     lib.hsp_spmm_buffer_bytes.argtypes = [vp]
     lib.hsp_spmm_buffer_bytes.restype = i64
+    lib.alg1_spmm.argtypes = [i64, vp, vp, vp, vp, vp, i32, i32, vp]
     return lib
 
 
@@ -262,6 +263,21 @@ def main(argv=None) -> int:
         print(f"[sweep] K={K} SELECTED V={sel.V} S={sel.S} SG={sel.SG} lpr={qs['lanes_per_row']} vec={qs['vec']} "
               f"rep={qs['rep']} gy={qs['grid_y']} waves={qs['waves_per_wg']}: {med:.4f} ms "
               f"({100 * (best_again or best[0]) / med:.1f}% of the sweep's best tuple re-timed)", flush=True)
+        if not args.no_hipsparse:
+            # the paper's Algorithm 1 as printed (one wavefront per row, one column per lane)
+            lib = _baseline_lib()
+            a1_best = None
+            for W in (1, 2, 4, 8):
+                Cd.fill_(float("nan"))
+                med, mn = time_launches(
+                    lambda: lib.alg1_spmm(g.n_rows, d_rowptr.data_ptr(), d_colidx.data_ptr(), d_vals.data_ptr(),
+                                          Bd.data_ptr(), Cd.data_ptr(), K, W, stream.cuda_stream),
+                    stream, torch, args.warmup, min(args.reps, 5))
+                dev = float((Cd - Cref).abs().max().item()) / scale if Cref is not None else None
+                emit(dict(base, kind="alg1", W=W, ms_median=med, ms_min=mn, gflops=flops / med / 1e6,
+                          max_rel_dev=dev))
+                a1_best = med if a1_best is None else min(a1_best, med)
+            print(f"[sweep] K={K} Algorithm 1 baseline: {a1_best:.4f} ms", flush=True)
         summary = dict(base, kind="summary", selected=selrec, pcsr_best=best[1], hipsparse_best=hs_best[1],
                        speedup_vs_hipsparse=(hs_best[0] / best[0]) if hs_best[1] and best[1] else None)
         emit(summary)

@@ -560,3 +560,35 @@ def test_seeded_random_configurations():
         h.close()
         done += 1
     assert done >= 80
+
+
+def test_parameterised_kernel_reduces_to_algorithm_1_bit_for_bit():
+    """Algorithm 2 with V=1, F=1, S=False is Algorithm 1 (Section 4.3).  On a matrix whose rows
+    all fit one chunk the two walk each row's nonzeros in the same order with the same fused
+    multiply-add, so the results must be identical bit patterns; the lane mapping (lanes per
+    row, vector width, waves per workgroup) must not matter."""
+    import ctypes
+
+    from paper_2605_15695_amd import sweep as sw
+
+    g = _graph("road")                                     # longest row: 8 nonzeros
+    assert g.degrees().max() <= 8
+    K = 96
+    B, ref, bound = _oracle("road", g, K, "normal")
+    lib = sw._baseline_lib()
+    d = [torch.from_numpy(x).cuda() for x in (g.rowptr, g.colidx, g.vals)]
+    Bd = torch.from_numpy(B).cuda()
+    C1 = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+    rc = lib.alg1_spmm(g.n_rows, d[0].data_ptr(), d[1].data_ptr(), d[2].data_ptr(), Bd.data_ptr(),
+                       C1.data_ptr(), K, 4, None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    _check(C1.cpu().numpy(), ref, bound, "Algorithm 1 baseline")
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=1, S=0))
+    for kern in [(64, 1, 1, 4), (8, 4, 1, 2), (16, 2, 1, 1), (32, 1, 1, 8), (8, 4, 4, 4)]:
+        pc.pcsr_set_kernel_params(h, *kern)
+        C2 = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+        pc.pcsr_spmm(h, Bd, C2, K)
+        torch.cuda.synchronize()
+        assert torch.equal(C1.view(torch.int32), C2.view(torch.int32)), kern
+    h.close()

@@ -35,5 +35,5 @@ def test_report_table_and_geomean(tmp_path):
     with redirect_stdout(out):
         assert report.main([str(p)]) == 0
     text = out.getvalue()
-    assert "| w | 64 | 100 | 1000 | 1,0,0 / 16,4,1,4,1 | 0.5000 |" in text
+    assert "| w | 64 | 100 | 1000 | 1,0,0 / 16,4,1,4,1 | 0.5000 |" in text and text.count("| - |") == 1
     assert "4.00x" in text and "**4.00x**" in text and "80.0 %" in text
