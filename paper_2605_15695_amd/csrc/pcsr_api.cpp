@@ -102,8 +102,8 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
             const int fit = (128 * 1024 / 4 / h->host.win_cols - 4) / vec;
             if (need > fit) need = fit;
         }
-        // balanced (power-law) handles: four items per wavefront, as pcsr_select picks
-        const int cap = h->host.S ? 16 : 64;
+        // balanced (power-law) handles: two or four items per wavefront, as pcsr_select picks
+        const int cap = h->host.S ? (h->host.nnz >= (int64_t(64) << 20) ? 16 : 32) : 64;
         lpr = 4;
         while (lpr < need && lpr < cap) lpr <<= 1;
     }
@@ -500,9 +500,9 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.
     const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
-    // Balanced power-law inputs do best with four items per wavefront (16 lanes each)
-    // whatever K is: repeats, then grid.y slices, cover the rest of the row.
-    const int lpr_cap = p.S ? 16 : 64;
+    // Balanced power-law inputs do best with several items per wavefront whatever K is
+    // (two below 64M nonzeros, four above): repeats, then grid.y slices, cover the row.
+    const int lpr_cap = p.S ? (nnz >= 64.0 * 1048576.0 ? 16 : 32) : 64;
     int lpr = 4;
     while (lpr * vec < K && lpr < lpr_cap) lpr <<= 1;
     int rep = 1;
