@@ -174,6 +174,15 @@ int pcsr_features(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *ro
                   const int32_t *colidx, int32_t omega, double *out, int32_t n_out);
 
 /*
+ * The same features computed by GPU kernels from CSR arrays that already live in device
+ * memory (rowptr, colidx: device; out: host).  The CSR is not validated here (pcsr_build
+ * does that); values agree with pcsr_features up to the rounding order of the fp64 sums.
+ * Synchronous.  Errors: INVALID_ARG, TOO_LARGE, OOM, HIP.
+ */
+int pcsr_features_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                         const int32_t *colidx, int32_t omega, double *out, int32_t n_out);
+
+/*
  * Configuration prediction (the role of the SpMM-decider, Section 5.2): maps the
  * feature vector and K to a full parameter tuple with a rule distilled from recorded
  * exhaustive sweeps on MI355X.  features: host fp64[PCSR_N_FEATURES]; out: host.

@@ -60,6 +60,7 @@ def _lib():
         lib.pcsr_window_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_double * 3)]
         lib.pcsr_export.argtypes = [vp, ctypes.POINTER(i64 * 6), vp, vp, vp, vp]
         lib.pcsr_features.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32]
+        lib.pcsr_features_device.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32]
         lib.pcsr_select.argtypes = [vp, i32, pp]
         lib.pcsr_reorder.argtypes = [i64, vp, vp, i32, vp, ctypes.POINTER(i64)]
         lib.pcsr_permute_csr.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
@@ -71,7 +72,7 @@ def _lib():
         lib.pcsr_last_hip_error.restype = ctypes.c_int
         for name in ("pcsr_build", "pcsr_spmm", "pcsr_free", "pcsr_set_kernel_params",
                      "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select",
-                     "pcsr_window_stats", "pcsr_reorder", "pcsr_permute_csr", "pcsr_transpose_csr"):
+                     "pcsr_window_stats", "pcsr_features_device", "pcsr_reorder", "pcsr_permute_csr", "pcsr_transpose_csr"):
             getattr(lib, name).restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -206,9 +207,18 @@ def pcsr_export(h: Handle) -> dict:
 
 
 def pcsr_features(n_rows, n_cols, rowptr, colidx, omega=0) -> np.ndarray:
-    k0, p_r, _ = _ptr(rowptr, np.dtype(np.int32))
-    k1, p_c, _ = _ptr(colidx, np.dtype(np.int32))
+    """Table 3 features; device tensors are routed to the GPU implementation."""
+    k0, p_r, dev_r = _ptr(rowptr, np.dtype(np.int32))
+    k1, p_c, dev_c = _ptr(colidx, np.dtype(np.int32))
     out = np.empty(PCSR_N_FEATURES, np.float64)
+    if dev_r or dev_c:
+        if not (dev_r and dev_c):
+            raise ValueError("rowptr and colidx must be both host or both device")
+        rc = _lib().pcsr_features_device(n_rows, n_cols, int(k1.shape[0]), p_r, p_c, omega, out.ctypes.data,
+                                         PCSR_N_FEATURES)
+        if rc != PCSR_OK:
+            raise PcsrError(rc, "pcsr_features_device")
+        return out
     rc = _lib().pcsr_features(n_rows, n_cols, int(k1.shape[0]), p_r, p_c, omega, out.ctypes.data,
                               PCSR_N_FEATURES)
     if rc != PCSR_OK:

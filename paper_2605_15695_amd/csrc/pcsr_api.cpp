@@ -474,6 +474,19 @@ int pcsr_features(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *ro
     }
 }
 
+int pcsr_features_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                         const int32_t *colidx, int32_t omega, double *out, int32_t n_out)
+{
+    if (!out || n_out < PCSR_N_FEATURES || !rowptr || omega < 0 || n_rows < 0 || n_cols < 0 || nnz < 0)
+        return PCSR_E_INVALID_ARG;
+    if (nnz > 0 && !colidx) return PCSR_E_INVALID_ARG;
+    if (nnz >= (int64_t(1) << 31) || n_rows >= (int64_t(1) << 31) - 1) return PCSR_E_TOO_LARGE;
+    int herr = 0;
+    int rc = pcsr::features_device(n_rows, n_cols, nnz, rowptr, colidx, omega, out, &herr);
+    if (rc == PCSR_E_HIP) g_last_hip = herr;
+    return rc;
+}
+
 int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
 {
     if (!f || !out) return PCSR_E_INVALID_ARG;

@@ -22,4 +22,9 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
                  const int32_t *d_colidx, const float *d_vals, int32_t V, int32_t S, int32_t SG,
                  int32_t omega, bool validate, DeviceBuild *out, int *hip_err);
 
+// Table 3 features (order as in pcsr.h) from CSR arrays in device memory.  The CSR is
+// assumed valid (pcsr_build validates).  Synchronous.
+int features_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_rowptr,
+                    const int32_t *d_colidx, int32_t omega, double *out, int *hip_err);
+
 } // namespace pcsr

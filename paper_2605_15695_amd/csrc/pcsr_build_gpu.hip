@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <hipcub/hipcub.hpp>
 
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 
@@ -158,6 +159,116 @@ __global__ void xcd_bounds_kernel(int32_t M, const int32_t *rowptr, int32_t *xb)
             lo = mid + 1;
     }
     xb[x] = (int32_t)lo;
+}
+
+
+// ---- Table 3 features on the GPU (two passes over the row pointer, one over colIdx)
+struct FeatAcc {
+    unsigned long long n_hat, nnz2, nonempty2, M1, M2;
+    int d_max;
+    int pad;
+    double bw_sum, bw_max, ss, ss_hat;
+};
+
+__device__ inline void atomic_max_double(double *addr, double v)
+{
+    unsigned long long *a = reinterpret_cast<unsigned long long *>(addr);
+    unsigned long long old = *a;
+    while (__longlong_as_double((long long)old) < v) {
+        const unsigned long long assumed = old;
+        old = atomicCAS(a, assumed, (unsigned long long)__double_as_longlong(v));
+        if (old == assumed) break;
+    }
+}
+
+// pass 1: one thread per row (degree, bandwidth) and, for even rows, the V = 2 panel length
+__global__ void features_pass1_kernel(int64_t n_rows, const int32_t *rowptr, const int32_t *colidx,
+                                      int32_t *len2, FeatAcc *acc)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int nh = 0, dmax = 0, ne2 = 0;
+    long l2 = 0;
+    double bw = 0.0;
+    if (i < n_rows) {
+        const int64_t s = rowptr[i], e = rowptr[i + 1];
+        const int l = (int)(e - s);
+        if (l > 0) {
+            nh = 1;
+            dmax = l;
+            bw = (double)colidx[e - 1] - (double)colidx[s];
+        }
+        if ((i & 1) == 0) {
+            int64_t a = s, ae = e, b = e, be = (i + 1 < n_rows) ? rowptr[i + 2] : e, n = 0;
+            while (a < ae && b < be) {
+                const int32_t ca = colidx[a], cb = colidx[b];
+                a += (ca <= cb);
+                b += (cb <= ca);
+                ++n;
+            }
+            l2 = n + (ae - a) + (be - b);
+            len2[i >> 1] = (int32_t)l2;
+            ne2 = l2 > 0;
+        }
+    }
+    typedef hipcub::BlockReduce<int, kThreads> RI;
+    typedef hipcub::BlockReduce<long, kThreads> RL;
+    typedef hipcub::BlockReduce<double, kThreads> RD;
+    __shared__ typename RI::TempStorage ti;
+    __shared__ typename RL::TempStorage tl;
+    __shared__ typename RD::TempStorage td;
+    const int s_nh = RI(ti).Sum(nh);
+    __syncthreads();
+    const int s_dmax = RI(ti).Reduce(dmax, hipcub::Max());
+    __syncthreads();
+    const int s_ne2 = RI(ti).Sum(ne2);
+    const long s_l2 = RL(tl).Sum(l2);
+    const double s_bw = RD(td).Sum(bw);
+    __syncthreads();
+    const double m_bw = RD(td).Reduce(bw, hipcub::Max());
+    if (threadIdx.x == 0) {
+        if (s_nh) atomicAdd(&acc->n_hat, (unsigned long long)s_nh);
+        if (s_dmax) atomicMax(&acc->d_max, s_dmax);
+        if (s_ne2) atomicAdd(&acc->nonempty2, (unsigned long long)s_ne2);
+        if (s_l2) atomicAdd(&acc->nnz2, (unsigned long long)s_l2);
+        if (s_bw != 0.0) atomicAdd(&acc->bw_sum, s_bw);
+        if (m_bw > 0.0) atomic_max_double(&acc->bw_max, m_bw);
+    }
+}
+
+// pass 2: squared deviations of the degrees and the item counts under Eq. (3)'s SG
+__global__ void features_pass2_kernel(int64_t n_rows, const int32_t *rowptr, const int32_t *len2, double d,
+                                      double d_hat, long sg1, long sg2, FeatAcc *acc)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    double ss = 0.0, ssh = 0.0;
+    long m1 = 0, m2 = 0;
+    if (i < n_rows) {
+        const long l = rowptr[i + 1] - rowptr[i];
+        ss = ((double)l - d) * ((double)l - d);
+        if (l > 0) ssh = ((double)l - d_hat) * ((double)l - d_hat);
+        m1 = (l + sg1 - 1) / sg1;
+        if (m1 < 1) m1 = 1;
+        if ((i & 1) == 0) {
+            m2 = (len2[i >> 1] + sg2 - 1) / sg2;
+            if (m2 < 1) m2 = 1;
+        }
+    }
+    typedef hipcub::BlockReduce<long, kThreads> RL;
+    typedef hipcub::BlockReduce<double, kThreads> RD;
+    __shared__ typename RL::TempStorage tl;
+    __shared__ typename RD::TempStorage td;
+    const double s_ss = RD(td).Sum(ss);
+    __syncthreads();
+    const double s_ssh = RD(td).Sum(ssh);
+    const long s_m1 = RL(tl).Sum(m1);
+    __syncthreads();
+    const long s_m2 = RL(tl).Sum(m2);
+    if (threadIdx.x == 0) {
+        atomicAdd(&acc->ss, s_ss);
+        atomicAdd(&acc->ss_hat, s_ssh);
+        atomicAdd(&acc->M1, (unsigned long long)s_m1);
+        atomicAdd(&acc->M2, (unsigned long long)s_m2);
+    }
 }
 
 struct Scratch { // frees everything it still owns on scope exit
@@ -343,6 +454,56 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
     sc.release(final_rowptr);
     sc.release(pcol);
     sc.release(pval);
+    return PCSR_OK;
+}
+
+int features_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_rowptr,
+                    const int32_t *d_colidx, int32_t omega, double *out, int *hip_err)
+{
+    if (omega == 0) omega = 64;
+    Scratch sc;
+    FeatAcc *d_acc = nullptr;
+    int32_t *len2 = nullptr;
+    const int64_t P2 = (n_rows + 1) / 2;
+    HIP_TRY(sc.alloc((void **)&d_acc, sizeof(FeatAcc)));
+    HIP_TRY(sc.alloc((void **)&len2, sizeof(int32_t) * (P2 + 1)));
+    HIP_TRY(hipMemset(d_acc, 0, sizeof(FeatAcc)));
+    FeatAcc h;
+    memset(&h, 0, sizeof(h));
+    if (n_rows > 0) {
+        hipLaunchKernelGGL(features_pass1_kernel, dim3(blocks_for(n_rows)), dim3(kThreads), 0, 0, n_rows,
+                           d_rowptr, d_colidx, len2, d_acc);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpy(&h, d_acc, sizeof(h), hipMemcpyDeviceToHost));
+    }
+    const double d = n_rows ? double(nnz) / double(n_rows) : 0.0;
+    const double d_hat = h.n_hat ? double(nnz) / double(h.n_hat) : 0.0;
+    auto eq3 = [&](int64_t v, int64_t ne) -> int64_t {
+        return (v == 0 || ne == 0) ? omega : ((v + ne * omega - 1) / (ne * omega)) * omega;
+    };
+    const int64_t sg1 = eq3(nnz, (int64_t)h.n_hat), sg2 = eq3((int64_t)h.nnz2, (int64_t)h.nonempty2);
+    if (n_rows > 0) {
+        hipLaunchKernelGGL(features_pass2_kernel, dim3(blocks_for(n_rows)), dim3(kThreads), 0, 0, n_rows,
+                           d_rowptr, len2, d, d_hat, (long)sg1, (long)sg2, d_acc);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipMemcpy(&h, d_acc, sizeof(h), hipMemcpyDeviceToHost));
+    }
+    out[0] = double(n_rows);
+    out[1] = double(h.n_hat);
+    out[2] = double(nnz);
+    out[3] = n_rows ? double(h.n_hat) / double(n_rows) : 0.0;
+    out[4] = d;
+    out[5] = d_hat;
+    out[6] = double(h.d_max);
+    out[7] = d > 0 ? sqrt(h.ss / double(n_rows)) / d : 0.0;
+    out[8] = h.n_hat ? sqrt(h.ss_hat / double(h.n_hat)) / d_hat : 0.0;
+    out[9] = n_rows ? double(h.M1) / double(n_rows) : 1.0;
+    out[10] = P2 ? double(h.M2) / double(P2) : 1.0;
+    out[11] = (n_rows && n_cols) ? double(nnz) / (double(n_rows) * double(n_cols)) : 0.0;
+    out[12] = n_rows ? h.bw_sum / double(n_rows) : 0.0;
+    out[13] = h.bw_max;
+    out[14] = 0.0;
+    out[15] = h.nnz2 ? 1.0 - double(nnz) / (double(h.nnz2) * 2.0) : 0.0;
     return PCSR_OK;
 }
 

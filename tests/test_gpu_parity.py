@@ -592,3 +592,17 @@ def test_parameterised_kernel_reduces_to_algorithm_1_bit_for_bit():
         torch.cuda.synchronize()
         assert torch.equal(C1.view(torch.int32), C2.view(torch.int32)), kern
     h.close()
+
+
+@pytest.mark.parametrize("name", ["poisson", "road", "rmat20", "sbm", "rmat22"])
+@pytest.mark.parametrize("omega", [32, 64])
+def test_gpu_side_features_match_reference(name, omega):
+    g = _graph(name)
+    f = pc.pcsr_features(g.n_rows, g.n_cols, torch.from_numpy(g.rowptr).cuda(),
+                         torch.from_numpy(g.colidx).cuda(), omega)
+    r = pf.features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega)
+    assert np.allclose(f, r, rtol=1e-11, atol=0), (f, r)
+    # degenerate shapes
+    z = pc.pcsr_features(3, 5, torch.zeros(4, dtype=torch.int32, device="cuda"),
+                         torch.zeros(0, dtype=torch.int32, device="cuda"), omega)
+    assert np.array_equal(z, pf.features(3, 5, np.zeros(4, np.int32), np.zeros(0, np.int32), omega))
