@@ -23,13 +23,20 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per SpMM launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
 # each scaled by what the counter reads for a plain copy kernel of known size); the
-# summaries with the commands are under profiles/.  Keyed by (workload, K).
+# summaries with the commands are under profiles/.  Keyed by workload, K and the kernel
+# instance that was profiled: a run that launches another instance reports null.
 PROFILED_TRAFFIC = {
-    ("road-full", 128): 2_121_501_891,      # profiles/spmm_road_K128.md
-    ("sbm-full", 256): 1_867_418_528,       # profiles/spmm_sbm_K256.md
-    ("rmat20-full", 64): 2_996_129_152,     # profiles/spmm_rmat20_K64.md
-    ("rmat22-full", 64): 29_434_107_301,    # profiles/spmm_rmat22_K64.md
 }
+
+
+def kernel_instance(V: int, S: int, launch: dict) -> str:
+    """Name of the SpMM kernel instance as rocprofv3 prints it."""
+    shape = f"{launch['lanes_per_row']}, {launch['vec']}, {launch['rep']}"
+    if launch["lds_bytes"]:
+        return f"spmm_window_kernel<{V}, {shape}>"
+    if launch["items_per_group"] > 1:
+        return f"spmm_batched_kernel<{V}, {shape}, {launch['items_per_group']}>"
+    return f"spmm_kernel<{V}, {'true' if S else 'false'}, {shape}>"
 
 
 def algorithmic_bytes(g, K: int) -> int:
@@ -44,8 +51,11 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="road", help="road | rmat20 | sbm | sbm_shuffled | poisson | rmat22")
-    ap.add_argument("--K", type=int, default=0, help="0 = the workload's benchmark width")
+    ap.add_argument("--workload", default="rmat22",
+                    help="rmat22 (default: the largest benchmark configuration) | road | rmat20 | sbm | "
+                         "sbm_shuffled | poisson")
+    ap.add_argument("--K", type=int, default=0,
+                    help="0 = the workload's benchmark width (the widest one, 512, for rmat22's K sweep)")
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--V", type=int, default=-1, help="-1 = library selector")
     ap.add_argument("--S", type=int, default=-1)
@@ -61,6 +71,8 @@ def main() -> int:
                     help="apply the library's locality reordering first (A' = P A P^T, B' = P B); the timed "
                          "SpMM runs on the relabelled problem and its result is checked as C = P^T C'")
     ap.add_argument("--no-xcd-remap", action="store_true")
+    ap.add_argument("--atomic-split", action="store_true",
+                    help="S = 1: accumulate split panels with fp32 atomics instead of the two-pass write-back")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--graph-batch", type=int, default=-1,
@@ -79,7 +91,7 @@ def main() -> int:
     import torch
 
     import paper_2605_15695_amd as pc
-    from paper_2605_15695_amd import synth
+    import synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -89,7 +101,7 @@ def main() -> int:
     t0 = time.time()
     g = synth.workload(args.workload, args.size)
     spec = synth.WORKLOADS[args.workload]
-    K = args.K or spec["K"][0]
+    K = args.K or max(spec["K"])
     B = synth.dense_operand(g.n_cols, K, spec["B"], 2)
     gen_s = time.time() - t0
 
@@ -118,11 +130,14 @@ def main() -> int:
         items_per_group=args.items_per_group or sel.items_per_group,
         col_window=sel.col_window if args.col_window < 0 else args.col_window,
         flags=(pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
-        | (pc.PCSR_FLAG_GPU_BUILD if args.gpu_build else 0))
+        | (pc.PCSR_FLAG_GPU_BUILD if args.gpu_build else 0)
+        | (pc.PCSR_FLAG_ATOMIC_SPLIT if args.atomic_split else 0))
     t0 = time.time()
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, params)
     build_ms = (time.time() - t0) * 1e3
     launch = pc.pcsr_query_launch(h, K)
+    instance = kernel_instance(V, S, launch)
+    pc.pcsr_reserve_workspace(h, K)
 
     Bd = torch.from_numpy(B).cuda()
     Cd = torch.empty((g.n_rows, K), dtype=torch.float32, device="cuda")
@@ -174,10 +189,11 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{args.workload}-{args.size}" + ("+reorder" if args.reorder else ""),
                    "graph": g.name, "n": g.n_rows,
-                   "nnz": g.nnz, "K": K, "V": V, "S": S, **launch},
+                   "nnz": g.nnz, "K": K, "V": V, "S": S, "SG": int(params.SG), **launch, "kernel": instance,
+                   "workspace_bytes": pc.pcsr_workspace_bytes(h, K)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": PROFILED_TRAFFIC.get((f"{args.workload}-{args.size}", K)),
+                     "traffic": PROFILED_TRAFFIC.get((f"{args.workload}-{args.size}", K, instance)),
                      "kernel_ms_mean": kern_ms, "kernel_ms_median": statistics.median(per_launch_ms),
                      "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": bytes_min},
         "setup": {"generate_s": gen_s, "features_select_ms": feat_ms, "pcsr_build_ms": build_ms,
@@ -218,6 +234,51 @@ def main() -> int:
                                "us_per_spmm_eager_events": kern_ms * 1e3,
                                "us_per_step_eager_wall": ms_per_step * 1e3}
 
+    # ---- the CPU oracle as it stands, on this machine's host cores, on a bounded sample of rows
+    rows = ref = bound = None
+    if not args.no_check or not args.no_cpu_baseline:
+        import oracle
+
+        if g.nnz * K <= 2.5e9:
+            sample, reps = "full workload, best of 3", 3
+        else:
+            n_s = max(1, int(g.n_rows * 2.5e9 / (g.nnz * K)))
+            rows = np.sort(np.random.default_rng(0).choice(g.n_rows, n_s, replace=False)).astype(np.int64)
+            sample, reps = f"{n_s} random rows of {g.n_rows}, 1 run", 1
+
+        def run_oracle(sel, n_threads=0):
+            t0 = time.perf_counter()
+            if sel is None:
+                r, b = oracle.spmm(g_orig.rowptr, g_orig.colidx, g_orig.vals, B_orig, n_threads=n_threads)
+            else:
+                r, b = oracle.spmm_rows(g_orig.rowptr, g_orig.colidx, g_orig.vals, B_orig, sel,
+                                        n_threads=n_threads)
+            return r, b, time.perf_counter() - t0
+
+        deg_orig = np.diff(g_orig.rowptr.astype(np.int64))
+        ncores = oracle.max_threads()            # read before the one-thread run lowers the setting
+        # one thread first (an eighth of the sample), then all cores
+        one_rows = (rows if rows is not None else np.arange(g.n_rows, dtype=np.int64))[::8]
+        _, _, t_one = run_oracle(one_rows, n_threads=1)
+        one_flops = 2.0 * float(deg_orig[one_rows].sum()) * K
+        best = float("inf")
+        for _ in range(reps):
+            ref, bound, t = run_oracle(rows, n_threads=ncores)
+            best = min(best, t)
+        cpu_flops = flops if rows is None else 2.0 * float(deg_orig[rows].sum()) * K
+        out["cpu_baseline"] = {"value": cpu_flops / best / 1e9, "unit": "GFLOP/s",
+                               "cores": ncores, "kind": "oracle", "sample": sample,
+                               "single_thread_value": one_flops / t_one / 1e9,
+                               "single_thread_sample": f"every 8th row of that sample ({one_rows.shape[0]} rows)"}
+
+    def sampled(Cx, relabelled):
+        """Rows of a device result that the oracle sample covers, in the oracle's row order."""
+        if rows is None:
+            got = Cx.cpu().numpy()
+            return got[perm] if (relabelled and perm is not None) else got
+        sel_rows = rows if (perm is None or not relabelled) else perm[rows].astype(np.int64)
+        return Cx[torch.from_numpy(sel_rows).cuda()].cpu().numpy()
+
     if not args.no_hipsparse:
         # vendor baseline on the same arrays (best of its CSR algorithms), outside the timed region
         import ctypes
@@ -227,7 +288,7 @@ def main() -> int:
         lib = sw._baseline_lib()
         d_csr = [torch.from_numpy(x).cuda() for x in (g.rowptr, g.colidx, g.vals)]
         Ch = torch.empty_like(Cd)
-        best_h = None
+        best_h, hs_ok = None, True
         for name, alg in sw.HIPSPARSE_ALGS.items():
             ctx = ctypes.c_void_p()
             rc = lib.hsp_spmm_create(g.n_rows, g.n_cols, g.nnz, d_csr[0].data_ptr(), d_csr[1].data_ptr(),
@@ -237,46 +298,21 @@ def main() -> int:
                 continue
             med, _ = sw.time_launches(lambda: lib.hsp_spmm_run(ctx), stream, torch, 3, 10)
             lib.hsp_spmm_destroy(ctx)
+            if ref is not None:
+                # hipSPARSE works on the (possibly relabelled) arrays the PCSR handle was built from
+                ok_h, _ = oracle.within_tolerance(sampled(Ch, True), ref, bound)
+                hs_ok = hs_ok and ok_h
             if best_h is None or med < best_h[1]:
                 best_h = (name, med)
         if best_h:
             out["hipsparse"] = {"alg": best_h[0], "ms": best_h[1], "gflops": flops / best_h[1] / 1e6,
                                 "pcsr_speedup": best_h[1] / kern_ms,
-                                "max_abs_diff_vs_pcsr": float((Ch - Cd).abs().max().item())}
+                                "max_abs_diff_vs_pcsr": float((Ch - Cd).abs().max().item()),
+                                "within_oracle_tolerance": bool(hs_ok) if ref is not None else None}
         del Ch, d_csr
 
-    if not args.no_check or not args.no_cpu_baseline:
-        import oracle
-
-        # the oracle as it stands, on this machine's host cores
-        if g.nnz * K <= 2.5e9:
-            rows, sample = None, "full workload, best of 3"
-            reps = 3
-        else:
-            n_s = max(1, int(g.n_rows * 2.5e9 / (g.nnz * K)))
-            rows = np.sort(np.random.default_rng(0).choice(g.n_rows, n_s, replace=False)).astype(np.int64)
-            sample, reps = f"{n_s} random rows of {g.n_rows}, 1 run", 1
-        best = float("inf")
-        for _ in range(reps):
-            t0 = time.perf_counter()
-            if rows is None:
-                ref, bound = oracle.spmm(g_orig.rowptr, g_orig.colidx, g_orig.vals, B_orig)
-            else:
-                ref, bound = oracle.spmm_rows(g_orig.rowptr, g_orig.colidx, g_orig.vals, B_orig, rows)
-            best = min(best, time.perf_counter() - t0)
-        # row i of the original problem is row perm[i] of the relabelled one
-        if rows is None:
-            cpu_flops = flops
-            got = Cd.cpu().numpy()
-            if perm is not None:
-                got = got[perm]
-        else:
-            cpu_flops = 2.0 * float(np.diff(g_orig.rowptr.astype(np.int64))[rows].sum()) * K
-            sel_rows = rows if perm is None else perm[rows].astype(np.int64)
-            got = Cd[torch.from_numpy(sel_rows).cuda()].cpu().numpy()
-        ok, worst = oracle.within_tolerance(got, ref, bound)
-        out["cpu_baseline"] = {"value": cpu_flops / best / 1e9, "unit": "GFLOP/s",
-                               "cores": oracle.max_threads(), "kind": "oracle", "sample": sample}
+    if ref is not None:
+        ok, worst = oracle.within_tolerance(sampled(Cd, True), ref, bound)
         out["parity"] = {"ok": bool(ok), "worst_err_over_limit": worst}
         if not ok:
             print(json.dumps(out))

@@ -39,9 +39,14 @@ enum {
     PCSR_FLAG_NO_XCD_REMAP = 4,/* keep the hardware's round-robin workgroup -> XCD order      */
     PCSR_FLAG_HOST_ONLY = 8,   /* build the arrays on the host only (no GPU needed); the
                                   handle serves pcsr_export but not pcsr_spmm                 */
-    PCSR_FLAG_GPU_BUILD = 16   /* generate the PCSR arrays with GPU kernels (host CSR arrays
+    PCSR_FLAG_GPU_BUILD = 16,  /* generate the PCSR arrays with GPU kernels (host CSR arrays
                                   are uploaded first).  CSR arrays given in device memory are
-                                  always built this way.  Not available with col_window       */
+                                  always built this way.  With col_window the flag is ignored:
+                                  windows are chosen on the host, and CSR arrays given in
+                                  device memory are copied to the host for that build        */
+    PCSR_FLAG_ATOMIC_SPLIT = 32 /* S = 1 only: panels that were split accumulate into C with
+                                  fp32 atomics, as Algorithm 2 prints it, instead of the
+                                  default two-pass write-back (see pcsr_spmm)                 */
 };
 
 /*
@@ -115,13 +120,34 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
  *      not overlap B.
  *   K  > 0.  One handle serves any K.
  *   stream  a hipStream_t (NULL = the null stream).  The work is enqueued there; the
- *      call does not wait for it and allocates nothing.
- * With S = 0 the result is bit-reproducible run to run.  With S = 1 rows that were
- * split are accumulated with fp32 atomics, so their summation order may vary.
+ *      call does not wait for it.
+ * Write-back (Algorithm 2, last block).  S = 0: one plain store per row of C.  S = 1: a
+ * panel that the workload split left whole is stored the same way; the items of a panel
+ * that was split each leave their partial rows in a workspace owned by the handle
+ * (V*K floats per such item) and a second kernel adds them in item order and stores the
+ * row once.  No atomics, no clearing of C: for a given handle, kernel parameters and K the
+ * result is the same bits on every run, for S = 0 and S = 1 alike.  With
+ * PCSR_FLAG_ATOMIC_SPLIT the split panels are cleared and accumulated with fp32 atomics
+ * instead (no workspace; summation order, hence the last bits, may vary between runs).
+ * Allocation: none, except that an S = 1 handle grows its workspace (a hipMalloc, after
+ * a hipFree that waits for the device) on the first call whose K needs more than any
+ * call before; pcsr_reserve_workspace does that ahead of time, e.g. before the stream
+ * is captured into a HIP graph.  Because of the workspace, SpMMs of one S = 1 handle must
+ * not overlap in time (two streams); different handles may.
  * Errors: INVALID_ARG (null or misaligned or overlapping B / C, handle built on another
- * device than the current one), UNSUPPORTED, HIP.
+ * device than the current one), UNSUPPORTED, OOM, HIP.
  */
 int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream);
+
+/*
+ * Workspace of the balanced write-back (see pcsr_spmm): bytes an SpMM of width K needs
+ * (0 for S = 0 handles and under PCSR_FLAG_ATOMIC_SPLIT), and a call that makes the
+ * handle's workspace at least that large now.  bytes: host.  pcsr_reserve_workspace
+ * allocates and may wait for the device; it must run on the handle's device.
+ * Errors: INVALID_ARG, UNSUPPORTED (K <= 0, host-only handle), OOM, HIP.
+ */
+int pcsr_workspace_bytes(pcsr_handle_t h, int32_t K, int64_t *bytes);
+int pcsr_reserve_workspace(pcsr_handle_t h, int32_t K);
 
 /* Releases the handle and its device arrays.  NULL is a no-op.  The caller must make
  * sure no pcsr_spmm using the handle is still running. */
@@ -129,7 +155,8 @@ int pcsr_free(pcsr_handle_t h);
 
 /*
  * Changes the kernel-only parameters (lanes_per_row, vec, rep, waves_per_wg,
- * items_per_group, and the PCSR_FLAG_NO_XCD_REMAP bit of flags) of an existing handle; 0 = auto.  The PCSR
+ * items_per_group, and the PCSR_FLAG_NO_XCD_REMAP and PCSR_FLAG_ATOMIC_SPLIT bits of
+ * flags) of an existing handle; 0 = auto.  The PCSR
  * arrays are untouched, so one build can be timed under many launch shapes (the
  * exhaustive sweep that stands in for the training data of Section 5.2).
  * Errors: INVALID_ARG, UNSUPPORTED.

@@ -1,10 +1,11 @@
 """PCSR SpMM for AMD MI355X: Python face of the C-ABI library libpcsr.so.
 
 The library is loaded on first use and there is no fallback: a missing or unloadable
-libpcsr.so raises.  `synth` holds the seeded input generators used by tests and bench.
+libpcsr.so raises.
 """
-from .binding import (FEATURE_NAMES, PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_GPU_BUILD, PCSR_FLAG_HOST_ONLY,  # noqa: F401
+from .binding import (FEATURE_NAMES, PCSR_FLAG_ATOMIC_SPLIT, PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_GPU_BUILD, PCSR_FLAG_HOST_ONLY,  # noqa: F401
                       PCSR_FLAG_NO_VALIDATE, PCSR_FLAG_NO_XCD_REMAP, Handle, PcsrError, make_params,
                       pcsr_build, pcsr_export, pcsr_features, pcsr_free, pcsr_mac_job_gap,
                       pcsr_params_t, pcsr_permute_csr, pcsr_query_launch, pcsr_reorder, pcsr_select, pcsr_set_kernel_params,
-                      pcsr_spmm, pcsr_strerror, pcsr_transpose_csr, pcsr_window_stats)
+                      pcsr_reserve_workspace, pcsr_spmm, pcsr_strerror, pcsr_transpose_csr, pcsr_window_stats,
+                      pcsr_workspace_bytes)

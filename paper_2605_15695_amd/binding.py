@@ -18,6 +18,7 @@ PCSR_E_INVALID_ARG, PCSR_E_BAD_CSR, PCSR_E_UNSUPPORTED = -1, -2, -3
 PCSR_E_TOO_LARGE, PCSR_E_OOM, PCSR_E_HIP = -4, -5, -6
 PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_NO_VALIDATE, PCSR_FLAG_NO_XCD_REMAP, PCSR_FLAG_HOST_ONLY = 1, 2, 4, 8
 PCSR_FLAG_GPU_BUILD = 16
+PCSR_FLAG_ATOMIC_SPLIT = 32
 PCSR_N_FEATURES = 16
 FEATURE_NAMES = ("n", "n_hat", "nnz", "delta", "d", "d_hat", "d_max", "CV", "CV_hat",
                  "SR_1", "SR_2", "rho", "b", "b_max", "PR_1", "PR_2")
@@ -55,6 +56,8 @@ def _lib():
         lib.pcsr_build.argtypes = [i64, i64, i64, vp, vp, vp, pp, ctypes.POINTER(vp)]
         lib.pcsr_spmm.argtypes = [vp, vp, vp, i32, vp]
         lib.pcsr_free.argtypes = [vp]
+        lib.pcsr_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(i64)]
+        lib.pcsr_reserve_workspace.argtypes = [vp, i32]
         lib.pcsr_set_kernel_params.argtypes = [vp, i32, i32, i32, i32, i32, i32]
         lib.pcsr_query_launch.argtypes = [vp, i32, ctypes.POINTER(i32 * 8)]
         lib.pcsr_window_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_double * 3)]
@@ -72,7 +75,8 @@ def _lib():
         lib.pcsr_last_hip_error.restype = ctypes.c_int
         for name in ("pcsr_build", "pcsr_spmm", "pcsr_free", "pcsr_set_kernel_params",
                      "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select",
-                     "pcsr_window_stats", "pcsr_features_device", "pcsr_reorder", "pcsr_permute_csr", "pcsr_transpose_csr"):
+                     "pcsr_window_stats", "pcsr_features_device", "pcsr_reorder", "pcsr_permute_csr",
+                     "pcsr_transpose_csr", "pcsr_workspace_bytes", "pcsr_reserve_workspace"):
             getattr(lib, name).restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -132,7 +136,9 @@ def pcsr_build(n_rows, n_cols, rowptr, colidx, vals, params=None) -> Handle:
         raise ValueError("rowptr must have n_rows + 1 entries")
     if k2 is not None and int(k2.shape[0]) != nnz:
         raise ValueError("vals and colidx differ in length")
-    p = params if params is not None else make_params()
+    p = pcsr_params_t()                      # a copy: the caller's struct is left as it is
+    ctypes.memmove(ctypes.byref(p), ctypes.byref(params if params is not None else make_params()),
+                   ctypes.sizeof(p))
     if dev_r or dev_c or dev_v:
         if not (dev_r and dev_c and dev_v):
             raise ValueError("CSR arrays must be all host or all device")
@@ -156,6 +162,20 @@ def pcsr_spmm(h: Handle, B, C, K: int, stream=None) -> None:
     rc = _lib().pcsr_spmm(h.raw, p_b, p_c, K, s)
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_spmm")
+
+
+def pcsr_workspace_bytes(h: Handle, K: int) -> int:
+    out = ctypes.c_int64(0)
+    rc = _lib().pcsr_workspace_bytes(h.raw, K, ctypes.byref(out))
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_workspace_bytes")
+    return int(out.value)
+
+
+def pcsr_reserve_workspace(h: Handle, K: int) -> None:
+    rc = _lib().pcsr_reserve_workspace(h.raw, K)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_reserve_workspace")
 
 
 def pcsr_free(h: Handle) -> None:

@@ -26,7 +26,9 @@ def _compile(src: str) -> pathlib.Path:
     if src.endswith(".hip"):
         cmd += DEVICE + os.environ.get("PCSR_EXTRA_HIPCC_FLAGS", "").split()
     cmd += ["-c", str(CSRC / src), "-o", str(obj)]
-    subprocess.run(cmd, check=True, stderr=subprocess.PIPE, text=True)
+    r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
     return obj
 
 

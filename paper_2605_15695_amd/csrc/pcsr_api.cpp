@@ -50,9 +50,14 @@ struct pcsr_handle_s {
     int32_t *d_colidx = nullptr;
     float *d_val = nullptr;
     int32_t *d_trow = nullptr;
-    int32_t *d_split = nullptr;
+    int32_t *d_split = nullptr;       // panels that own more than one item, ascending
+    int32_t *d_split_first = nullptr; // their first items
+    int32_t *d_split_slot = nullptr;  // their first workspace slots (n_split + 1 entries)
     int32_t *d_win = nullptr;
     int64_t n_split = 0;
+    int64_t n_split_items = 0; // workspace slots: items that belong to split panels
+    float *d_ws = nullptr;     // partial rows of those items, grown on demand
+    size_t ws_bytes = 0;
     int32_t lpr = 0, vec = 0, rep = 0, waves = 0, ipg = 0, flags = 0;
 };
 
@@ -67,9 +72,14 @@ void release_device(pcsr_handle_t h)
     if (h->d_val) (void)hipFree(h->d_val);
     if (h->d_trow) (void)hipFree(h->d_trow);
     if (h->d_split) (void)hipFree(h->d_split);
+    if (h->d_split_first) (void)hipFree(h->d_split_first);
+    if (h->d_split_slot) (void)hipFree(h->d_split_slot);
     if (h->d_win) (void)hipFree(h->d_win);
+    if (h->d_ws) (void)hipFree(h->d_ws);
     h->d_rowptr = h->d_colidx = h->d_trow = h->d_split = h->d_win = nullptr;
-    h->d_val = nullptr;
+    h->d_split_first = h->d_split_slot = nullptr;
+    h->d_val = h->d_ws = nullptr;
+    h->ws_bytes = 0;
 }
 
 template <class T> int upload(const std::vector<T> &src, T **dst)
@@ -232,6 +242,8 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             (void)hipFree(db.val);
             if (db.trow) (void)hipFree(db.trow);
             if (db.split) (void)hipFree(db.split);
+            if (db.split_first) (void)hipFree(db.split_first);
+            if (db.split_slot) (void)hipFree(db.split_slot);
             return PCSR_E_OOM;
         }
         h->host.n_rows = n_rows;
@@ -250,7 +262,10 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         h->d_val = db.val;
         h->d_trow = db.trow;
         h->d_split = db.split;
+        h->d_split_first = db.split_first;
+        h->d_split_slot = db.split_slot;
         h->n_split = db.n_split;
+        h->n_split_items = db.n_split_items;
         h->lpr = prm.lanes_per_row;
         h->vec = prm.vec;
         h->rep = prm.rep;
@@ -267,8 +282,24 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     }
 
     try {
-        // CSR arrays handed over in device memory are staged on the host first (only the
-        // column-window build still needs them there)
+        // The column-window build runs on the host: CSR arrays handed over in device memory
+        // are copied there first (every other device-CSR build took the GPU branch above).
+        std::vector<int32_t> s_rowptr, s_colidx;
+        std::vector<float> s_vals;
+        if (device_csr) {
+            s_rowptr.resize(n_rows + 1);
+            s_colidx.resize(nnz);
+            s_vals.resize(nnz);
+            if (!hip_ok(hipMemcpy(s_rowptr.data(), rowptr, sizeof(int32_t) * (n_rows + 1), hipMemcpyDeviceToHost)))
+                return PCSR_E_HIP;
+            if (nnz > 0 &&
+                (!hip_ok(hipMemcpy(s_colidx.data(), colidx, sizeof(int32_t) * nnz, hipMemcpyDeviceToHost)) ||
+                 !hip_ok(hipMemcpy(s_vals.data(), vals, sizeof(float) * nnz, hipMemcpyDeviceToHost))))
+                return PCSR_E_HIP;
+            rowptr = s_rowptr.data();
+            colidx = s_colidx.data();
+            vals = s_vals.data();
+        }
         if (!(prm.flags & PCSR_FLAG_NO_VALIDATE)) {
             rc = pcsr::validate_csr(n_rows, n_cols, nnz, rowptr, colidx);
             if (rc != PCSR_OK) return rc;
@@ -298,6 +329,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         h->ipg = prm.items_per_group;
         h->flags = prm.flags;
         h->n_split = (int64_t)h->host.split_panels.size();
+        h->n_split_items = h->host.split_slot.empty() ? 0 : h->host.split_slot.back();
         if (!host_only) {
             if (!hip_ok(hipGetDevice(&h->device))) {
                 delete h;
@@ -308,6 +340,8 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             if (rc == PCSR_OK) rc = upload(h->host.val, &h->d_val);
             if (rc == PCSR_OK && h->host.S) rc = upload(h->host.trow, &h->d_trow);
             if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_panels, &h->d_split);
+            if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_first, &h->d_split_first);
+            if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_slot, &h->d_split_slot);
             if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_start, &h->d_win);
             if (rc != PCSR_OK) {
                 release_device(h);
@@ -320,6 +354,8 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             std::vector<float>().swap(h->host.val);
             std::vector<int32_t>().swap(h->host.trow);
             std::vector<int32_t>().swap(h->host.split_panels);
+            std::vector<int32_t>().swap(h->host.split_first);
+            std::vector<int32_t>().swap(h->host.split_slot);
             std::vector<int32_t>().swap(h->host.win_start);
         }
         *out = h;
@@ -329,34 +365,47 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     }
 }
 
-int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream)
+// Bytes of workspace one SpMM of width K needs: V*K floats per item of a split panel
+// (deterministic balanced write-back only).
+static int64_t workspace_need(pcsr_handle_t h, int32_t K)
+{
+    if (!h->host.S || (h->flags & PCSR_FLAG_ATOMIC_SPLIT)) return 0;
+    return h->n_split_items * (int64_t)h->host.V * (int64_t)K * (int64_t)sizeof(float);
+}
+
+// Checks shared by the SpMM entry points; resolves the launch shape.
+static int spmm_check(pcsr_handle_t h, const float *B, float *C, int32_t K, pcsr::LaunchShape *ls)
 {
     if (!valid(h)) return PCSR_E_INVALID_ARG;
     if (h->host_only) return PCSR_E_UNSUPPORTED;
     if (K <= 0) return PCSR_E_UNSUPPORTED;
     if (!C && h->host.n_rows > 0) return PCSR_E_INVALID_ARG;
     if (!B && h->host.n_cols > 0 && h->host.nnz_v > 0) return PCSR_E_INVALID_ARG;
-    pcsr::LaunchShape ls;
-    int rc = resolve_launch(h, K, &ls);
+    int rc = resolve_launch(h, K, ls);
     if (rc != PCSR_OK) return rc;
-    const uintptr_t align = 4u * (unsigned)ls.vec;
+    const uintptr_t align = 4u * (unsigned)ls->vec;
     if ((reinterpret_cast<uintptr_t>(B) % align) || (reinterpret_cast<uintptr_t>(C) % align))
         return PCSR_E_INVALID_ARG;
     if (h->host.n_rows == 0) return PCSR_OK;
-    {
-        // B and C may not overlap: the kernel reads B while other workgroups write C
-        const uintptr_t b0 = reinterpret_cast<uintptr_t>(B), c0 = reinterpret_cast<uintptr_t>(C);
-        const uintptr_t b1 = b0 + (uintptr_t)h->host.n_cols * (uintptr_t)K * 4u;
-        const uintptr_t c1 = c0 + (uintptr_t)h->host.n_rows * (uintptr_t)K * 4u;
-        if (b0 < c1 && c0 < b1 && h->host.n_cols > 0) return PCSR_E_INVALID_ARG;
-        // the handle's arrays live on the device that was current at pcsr_build
-        int dev = -1;
-        if (!hip_ok(hipGetDevice(&dev))) return PCSR_E_HIP;
-        if (dev != h->device) return PCSR_E_INVALID_ARG;
-    }
+    // B and C may not overlap: the kernel reads B while other workgroups write C
+    const uintptr_t b0 = reinterpret_cast<uintptr_t>(B), c0 = reinterpret_cast<uintptr_t>(C);
+    const uintptr_t b1 = b0 + (uintptr_t)h->host.n_cols * (uintptr_t)K * 4u;
+    const uintptr_t c1 = c0 + (uintptr_t)h->host.n_rows * (uintptr_t)K * 4u;
+    if (b0 < c1 && c0 < b1 && h->host.n_cols > 0) return PCSR_E_INVALID_ARG;
+    // the handle's arrays live on the device that was current at pcsr_build
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev))) return PCSR_E_HIP;
+    if (dev != h->device) return PCSR_E_INVALID_ARG;
+    return PCSR_OK;
+}
 
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (h->host.S && h->n_split > 0) {
+// Enqueues the kernels of one SpMM.  ws: workspace of at least workspace_need(h, K) bytes
+// (ignored when that is 0).
+static int spmm_enqueue(pcsr_handle_t h, const float *B, float *C, int32_t K, const pcsr::LaunchShape &ls,
+                        float *ws, hipStream_t s)
+{
+    const bool two_pass = workspace_need(h, K) > 0;
+    if (h->host.S && h->n_split > 0 && !two_pass) {
         if (!hip_ok(pcsr::launch_zero_panels(h->d_split, h->n_split, h->host.V, C,
                                              (int32_t)h->host.n_rows, K, s)))
             return PCSR_E_HIP;
@@ -374,12 +423,76 @@ int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream
     a.nblk = ls.grid_x;
     a.xcd_remap = (h->flags & PCSR_FLAG_NO_XCD_REMAP) ? 0 : 1;
     for (int x = 0; x < 9; ++x) a.xb[x] = h->host.xcd_bounds[x];
+    a.ws = two_pass ? ws : nullptr;
+    a.split_panels = h->d_split;
+    a.split_first = h->d_split_first;
+    a.split_slot = h->d_split_slot;
+    a.n_split = (int32_t)h->n_split;
     a.win_start = h->d_win;
     a.win_cols = h->host.win_cols;
     a.win_items = h->host.win_items;
     a.n_cols = (int32_t)h->host.n_cols;
     if (!hip_ok(pcsr::launch_spmm(h->host.V, h->host.S, ls, a, s))) return PCSR_E_HIP;
+    if (two_pass) {
+        if (!hip_ok(pcsr::launch_reduce_split(h->d_split, h->d_split_slot, h->n_split, h->host.V, ws, C,
+                                              (int32_t)h->host.n_rows, K, s)))
+            return PCSR_E_HIP;
+    }
     return PCSR_OK;
+}
+
+// Makes the handle's own workspace at least `need` bytes.  Allocates, so not for use
+// under stream capture.
+static int grow_workspace(pcsr_handle_t h, int64_t need)
+{
+    if (need <= (int64_t)h->ws_bytes) return PCSR_OK;
+    if (h->d_ws) {
+        // hipFree waits for the device, so no earlier SpMM still uses the old block
+        if (!hip_ok(hipFree(h->d_ws))) return PCSR_E_HIP;
+        h->d_ws = nullptr;
+        h->ws_bytes = 0;
+    }
+    hipError_t e = hipMalloc((void **)&h->d_ws, (size_t)need);
+    if (e == hipErrorOutOfMemory) {
+        (void)hipGetLastError();
+        h->d_ws = nullptr;
+        return PCSR_E_OOM;
+    }
+    if (!hip_ok(e)) {
+        h->d_ws = nullptr;
+        return PCSR_E_HIP;
+    }
+    h->ws_bytes = (size_t)need;
+    return PCSR_OK;
+}
+
+int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream)
+{
+    pcsr::LaunchShape ls;
+    int rc = spmm_check(h, B, C, K, &ls);
+    if (rc != PCSR_OK) return rc;
+    if (h->host.n_rows == 0) return PCSR_OK;
+    rc = grow_workspace(h, workspace_need(h, K));
+    if (rc != PCSR_OK) return rc;
+    return spmm_enqueue(h, B, C, K, ls, h->d_ws, static_cast<hipStream_t>(stream));
+}
+
+int pcsr_workspace_bytes(pcsr_handle_t h, int32_t K, int64_t *bytes)
+{
+    if (!valid(h) || !bytes) return PCSR_E_INVALID_ARG;
+    if (K <= 0) return PCSR_E_UNSUPPORTED;
+    *bytes = workspace_need(h, K);
+    return PCSR_OK;
+}
+
+int pcsr_reserve_workspace(pcsr_handle_t h, int32_t K)
+{
+    if (!valid(h)) return PCSR_E_INVALID_ARG;
+    if (h->host_only || K <= 0) return PCSR_E_UNSUPPORTED;
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev))) return PCSR_E_HIP;
+    if (dev != h->device) return PCSR_E_INVALID_ARG;
+    return grow_workspace(h, workspace_need(h, K));
 }
 
 int pcsr_free(pcsr_handle_t h)
@@ -403,7 +516,8 @@ int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, 
     h->rep = rep;
     h->waves = waves_per_wg;
     h->ipg = items_per_group;
-    h->flags = (h->flags & ~PCSR_FLAG_NO_XCD_REMAP) | (flags & PCSR_FLAG_NO_XCD_REMAP);
+    constexpr int32_t kLaunchFlags = PCSR_FLAG_NO_XCD_REMAP | PCSR_FLAG_ATOMIC_SPLIT;
+    h->flags = (h->flags & ~kLaunchFlags) | (flags & kLaunchFlags);
     return PCSR_OK;
 }
 

@@ -10,8 +10,10 @@ struct DeviceBuild {
     int32_t *colidx = nullptr; // nnz_v
     float *val = nullptr;      // nnz_v * V
     int32_t *trow = nullptr;   // M (S only)
-    int32_t *split = nullptr;  // panels with more than one item (S only), n_split entries
-    int64_t P = 0, M = 0, nnz_v = 0, n_split = 0, max_item_len = 0;
+    int32_t *split = nullptr;  // panels with more than one item (S only), ascending, n_split entries
+    int32_t *split_first = nullptr; // first item of each of them, n_split entries
+    int32_t *split_slot = nullptr;  // first workspace slot of each of them, n_split + 1 entries
+    int64_t P = 0, M = 0, nnz_v = 0, n_split = 0, n_split_items = 0, max_item_len = 0;
     int32_t SG = 0;
     int32_t xcd_bounds[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 };

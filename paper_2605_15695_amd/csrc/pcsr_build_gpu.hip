@@ -117,10 +117,9 @@ __global__ void items_kernel(int64_t P, const int32_t *prow, int32_t sg, int32_t
     items[p] = it > 1 ? it : 1;
 }
 
-// rewritten rowPtr, TRow, and the list of panels that own more than one item
+// rewritten rowPtr and TRow
 __global__ void split_fill_kernel(int64_t P, const int32_t *prow, const int32_t *first, int32_t sg,
-                                  int32_t *out_rowptr, int32_t *out_trow, int32_t *split_list,
-                                  int *n_split)
+                                  int32_t *out_rowptr, int32_t *out_trow)
 {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p >= P) return;
@@ -131,8 +130,37 @@ __global__ void split_fill_kernel(int64_t P, const int32_t *prow, const int32_t 
         out_trow[it] = (int32_t)p;
         start += sg;
     }
-    if (i1 - i0 > 1) split_list[atomicAdd(n_split, 1)] = (int32_t)p;
     if (p == P - 1) out_rowptr[i1] = prow[P];
+}
+
+// Panels that own more than one item, in ascending order (positions come from scans, so
+// the tables are the same on every run): mark[p] = 1 and cnt[p] = items for such a panel.
+__global__ void split_marks_kernel(int64_t P, const int32_t *items, int32_t *mark, int32_t *cnt)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > P) return;
+    const int it = p < P ? items[p] : 0;
+    mark[p] = it > 1 ? 1 : 0;
+    cnt[p] = it > 1 ? it : 0;
+}
+
+// qpos / slotbase: exclusive scans of mark / cnt over P + 1 entries
+__global__ void split_tables_kernel(int64_t P, const int32_t *items, const int32_t *first, const int32_t *qpos,
+                                    const int32_t *slotbase, int32_t *split_panels, int32_t *split_first,
+                                    int32_t *split_slot)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p > P) return;
+    if (p == P) {
+        split_slot[qpos[P]] = slotbase[P];
+        return;
+    }
+    if (items[p] > 1) {
+        const int q = qpos[p];
+        split_panels[q] = (int32_t)p;
+        split_first[q] = first[p];
+        split_slot[q] = slotbase[p];
+    }
 }
 
 // 8 contiguous item ranges of equal work (vectors + 8 per item); same rule as the host builder
@@ -332,7 +360,7 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
     HIP_TRY(hipMemcpy(&ends[1], d_rowptr + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost));
     if (ends[0] != 0 || ends[1] != nnz) return PCSR_E_BAD_CSR;
 
-    int *d_flags = nullptr; // [0] bad csr, [1] longest panel, [2] split count; [4..5] nonempty (64 bit)
+    int *d_flags = nullptr; // [0] bad csr, [1] longest panel; [4..5] nonempty (64 bit)
     HIP_TRY(sc.alloc((void **)&d_flags, 8 * sizeof(int)));
     HIP_TRY(hipMemset(d_flags, 0, 8 * sizeof(int)));
     if (validate && n_rows > 0) {
@@ -399,8 +427,11 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
     out->nnz_v = nnz_v;
     out->SG = (int32_t)sg;
     out->n_split = 0;
+    out->n_split_items = 0;
     out->trow = nullptr;
     out->split = nullptr;
+    out->split_first = nullptr;
+    out->split_slot = nullptr;
 
     int32_t *final_rowptr = prow;
     int64_t M = P;
@@ -418,25 +449,48 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
         int32_t m32 = 0;
         HIP_TRY(hipMemcpy(&m32, first + P, sizeof(int32_t), hipMemcpyDeviceToHost));
         M = m32;
-        int32_t *srow = nullptr, *trow = nullptr, *split = nullptr;
+        int32_t *srow = nullptr, *trow = nullptr;
         HIP_TRY(sc.alloc((void **)&srow, sizeof(int32_t) * (M + 1)));
         HIP_TRY(sc.alloc((void **)&trow, sizeof(int32_t) * (M + 1)));
-        HIP_TRY(sc.alloc((void **)&split, sizeof(int32_t) * (P + 1)));
         if (P > 0) {
             hipLaunchKernelGGL(split_fill_kernel, dim3(blocks_for(P)), dim3(kThreads), 0, 0, P, prow, first,
-                               (int32_t)sg, srow, trow, split, d_flags + 2);
+                               (int32_t)sg, srow, trow);
             HIP_TRY(hipGetLastError());
         } else {
             HIP_TRY(hipMemset(srow, 0, sizeof(int32_t)));
         }
-        int n_split = 0;
-        HIP_TRY(hipMemcpy(&n_split, d_flags + 2, sizeof(int), hipMemcpyDeviceToHost));
+        // tables of the split panels: panel, first item, first workspace slot
+        int32_t *mark = nullptr, *cnt = nullptr, *qpos = nullptr, *slotbase = nullptr;
+        HIP_TRY(sc.alloc((void **)&mark, sizeof(int32_t) * (P + 1)));
+        HIP_TRY(sc.alloc((void **)&cnt, sizeof(int32_t) * (P + 1)));
+        HIP_TRY(sc.alloc((void **)&qpos, sizeof(int32_t) * (P + 1)));
+        HIP_TRY(sc.alloc((void **)&slotbase, sizeof(int32_t) * (P + 1)));
+        hipLaunchKernelGGL(split_marks_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, items, mark,
+                           cnt);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(exclusive_scan(mark, qpos, P + 1, sc));
+        HIP_TRY(exclusive_scan(cnt, slotbase, P + 1, sc));
+        int32_t n_split = 0, n_split_items = 0;
+        HIP_TRY(hipMemcpy(&n_split, qpos + P, sizeof(int32_t), hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(&n_split_items, slotbase + P, sizeof(int32_t), hipMemcpyDeviceToHost));
+        int32_t *split = nullptr, *split_first = nullptr, *split_slot = nullptr;
+        HIP_TRY(sc.alloc((void **)&split, sizeof(int32_t) * (n_split + 1)));
+        HIP_TRY(sc.alloc((void **)&split_first, sizeof(int32_t) * (n_split + 1)));
+        HIP_TRY(sc.alloc((void **)&split_slot, sizeof(int32_t) * (n_split + 1)));
+        hipLaunchKernelGGL(split_tables_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, items, first,
+                           qpos, slotbase, split, split_first, split_slot);
+        HIP_TRY(hipGetLastError());
         out->n_split = n_split;
+        out->n_split_items = n_split_items;
         out->max_item_len = sg < nnz_v ? sg : nnz_v;
         out->trow = trow;
         out->split = split;
+        out->split_first = split_first;
+        out->split_slot = split_slot;
         sc.release(trow);
         sc.release(split);
+        sc.release(split_first);
+        sc.release(split_slot);
         final_rowptr = srow;
     }
     out->M = M;

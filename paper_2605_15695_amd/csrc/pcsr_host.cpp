@@ -174,12 +174,20 @@ int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         // ---- workload split: panel with l vectors -> max(1, ceil(l/SG)) items
         std::vector<int64_t> first(P + 1);
         first[0] = 0;
+        int64_t slots = 0; // items of split panels seen so far (<= M)
         for (int64_t p = 0; p < P; ++p) {
             int64_t l = prow[p + 1] - prow[p];
             int64_t items = std::max<int64_t>(1, ceildiv(l, sg));
             first[p + 1] = first[p] + items;
-            if (items > 1) h.split_panels.push_back((int32_t)p);
+            if (items > 1) {
+                if (first[p] >= (int64_t(1) << 31) - 1) return PCSR_E_TOO_LARGE;
+                h.split_panels.push_back((int32_t)p);
+                h.split_first.push_back((int32_t)first[p]);
+                h.split_slot.push_back((int32_t)slots);
+                slots += items;
+            }
         }
+        h.split_slot.push_back((int32_t)slots);
         const int64_t M = first[P];
         if (M >= (int64_t(1) << 31) - 1) return PCSR_E_TOO_LARGE;
         h.M = M;

@@ -19,6 +19,10 @@ struct HostPcsr {
     // Not part of the format: panels that own more than one work item.  Their C rows
     // are cleared before the kernel accumulates into them.
     std::vector<int32_t> split_panels;
+    // For the q-th such panel: its first work item, and the first of the consecutive
+    // workspace slots its items write their partial rows to (split_slot has one more
+    // entry: the total number of items that belong to split panels).
+    std::vector<int32_t> split_first, split_slot;
     int64_t max_item_len = 0;
     // Not part of the format: item boundaries that cut the item sequence into 8 contiguous
     // ranges of equal work (vectors plus a per-item overhead), one per XCD.

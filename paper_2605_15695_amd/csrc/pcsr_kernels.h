@@ -19,6 +19,14 @@ struct SpmmArgs {
     int32_t nblk;      // grid.x
     int32_t xcd_remap; // 1: one contiguous, work-balanced item range per XCD
     int32_t xb[9];     // item range [xb[x], xb[x+1]) of XCD x (xcd_remap only)
+    // Balanced handles, deterministic write-back: an item of a panel that was split over
+    // several items stores its partial rows in `ws` (slot-major: (slot*V + v)*K + k) and
+    // reduce_split adds them in item order.  ws == nullptr selects the atomic write-back.
+    float *ws;
+    const int32_t *split_panels; // n_split, ascending: panels that own more than one item
+    const int32_t *split_first;  // n_split: first item of each such panel
+    const int32_t *split_slot;   // n_split + 1: first workspace slot of each such panel
+    int32_t n_split;
     // column-window blocking (window kernel only)
     const int32_t *win_start; // per item block: first column of the staged window or -1
     int32_t win_cols;         // rows of B staged in LDS
@@ -45,5 +53,12 @@ hipError_t launch_spmm(int V, int S, const LaunchShape &ls, const SpmmArgs &args
 // Clears the C rows of the listed panels (rows panel*V .. panel*V+V-1, K floats each).
 hipError_t launch_zero_panels(const int32_t *panels, int64_t n_panels, int V, float *C,
                               int32_t n_rows, int32_t K, hipStream_t stream);
+
+// Second pass of the deterministic balanced write-back: for every split panel q and
+// v < V, C[panel*V + v][:] = sum over its items, in item order, of the partial rows the
+// SpMM kernel left in ws.
+hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split_slot, int64_t n_split,
+                               int V, const float *ws, float *C, int32_t n_rows, int32_t K,
+                               hipStream_t stream);
 
 } // namespace pcsr

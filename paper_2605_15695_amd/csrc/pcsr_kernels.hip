@@ -84,6 +84,25 @@ template <int VEC> __device__ __forceinline__ void store_vec(float *p, const flo
 #endif
 }
 
+// cacheable store: workspace partials are read back by the next kernel
+template <int VEC> __device__ __forceinline__ void store_vec_cached(float *p, const float (&s)[VEC])
+{
+    using T = typename Vec<VEC>::type;
+    T t;
+    if constexpr (VEC == 1) {
+        t = s[0];
+    } else if constexpr (VEC == 2) {
+        t.x = s[0];
+        t.y = s[1];
+    } else {
+        t.x = s[0];
+        t.y = s[1];
+        t.z = s[2];
+        t.w = s[3];
+    }
+    *reinterpret_cast<T *>(p) = t;
+}
+
 // colIdx / val are read exactly once per SpMM: keep them from displacing B rows in L2
 template <class T> __device__ __forceinline__ T stream_load(const T *p)
 {
@@ -229,8 +248,10 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
                 for (int e = 0; e < VEC; ++e) acc[v][r][e] += part[v][r][e];
     }
 
-    // write-back (Algorithm 2, last block): plain store, or accumulate into the panel
-    // named by TRow when the panel was split over several items
+    // write-back (Algorithm 2, last block): plain store for an item that is the only one
+    // of its panel.  An item of a panel that was split (TRow names the panel) either
+    // leaves its partial rows in the workspace slot that belongs to it, for the second
+    // pass to add in item order, or, without a workspace, accumulates with atomics.
     int panel = item;
     bool sole = true;
     if constexpr (S) {
@@ -239,16 +260,34 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
         const bool same_next = item + 1 < a.M && a.trow[item + 1] == panel;
         sole = !(same_prev || same_next);
     }
+    float *wrow = nullptr;
+    if constexpr (S) {
+        if (!sole && a.ws) {
+            // position of the panel in the ascending list of split panels
+            int lo = 0, hi = a.n_split - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (a.split_panels[mid] < panel)
+                    lo = mid + 1;
+                else
+                    hi = mid;
+            }
+            const long slot = (long)a.split_slot[lo] + (item - a.split_first[lo]);
+            wrow = a.ws + slot * V * K;
+        }
+    }
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const long row = (long)panel * V + v;
         if (row < a.n_rows) {
-            float *crow = a.C + row * K;
+            float *crow = wrow ? wrow + v * K : a.C + row * K;
 #pragma unroll
             for (int r = 0; r < REP; ++r) {
                 if (kv[r]) {
                     if (sole) {
                         store_vec<VEC>(crow + kc[r], acc[v][r]);
+                    } else if (wrow) {
+                        store_vec_cached<VEC>(crow + kc[r], acc[v][r]);
                     } else {
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) atomicAdd(crow + kc[r] + e, acc[v][r][e]);
@@ -263,8 +302,9 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
 // Batched walk for matrices of short rows (no balancing): one lane group owns IPG
 // consecutive work items and walks their joint colIdx/val range as one stream, so the
 // gathers of several rows are in flight together.  Every entry carries the index of the
-// item it belongs to; an entry's value is masked into the accumulator of its own item
-// only (IPG-fold FMA work, irrelevant next to the memory time of short rows).
+// item it belongs to and only that item's accumulator takes the multiply-add (a select,
+// not a multiplication by zero: a non-finite B row must not leak into rows that do not
+// reference it).  IPG-fold ALU work, irrelevant next to the memory time of short rows.
 template <int V, int LPR, int VEC, int REP, int IPG>
 __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
 {
@@ -367,12 +407,14 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
                 for (int i = 0; i < IPG; ++i)
 #pragma unroll
                     for (int v = 0; v < V; ++v) {
-                        const float m = tj[u] == i ? aj[u][v] : 0.0f;
+                        const bool mine = tj[u] == i;
 #pragma unroll
                         for (int r = 0; r < REP; ++r)
 #pragma unroll
-                            for (int e = 0; e < VEC; ++e)
-                                acc[i][v][r][e] = fmaf(m, b[u][r][e], acc[i][v][r][e]);
+                            for (int e = 0; e < VEC; ++e) {
+                                const float t = fmaf(aj[u][v], b[u][r][e], acc[i][v][r][e]);
+                                acc[i][v][r][e] = mine ? t : acc[i][v][r][e];
+                            }
                     }
         }
     }
@@ -576,6 +618,40 @@ __global__ void __launch_bounds__(256) zero_panels_kernel(const int32_t *__restr
     }
 }
 
+// One thread per element (q, v, k) of the rows of split panels.  The partial rows of
+// panel q sit in consecutive workspace slots in item order and are added in that order,
+// whatever the grid looks like, so the balanced result is the same bits on every run.
+__global__ void __launch_bounds__(256) reduce_split_kernel(const int32_t *__restrict__ split_panels,
+                                                           const int32_t *__restrict__ split_slot,
+                                                           long n_split, int V, const float *__restrict__ ws,
+                                                           float *C, int n_rows, int K)
+{
+    const long total = n_split * V * (long)K;
+    for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total;
+         t += (long)gridDim.x * blockDim.x) {
+        const long r = t / K;
+        const int k = (int)(t - r * K);
+        const long q = r / V;
+        const int v = (int)(r - q * V);
+        const long row = (long)split_panels[q] * V + v;
+        if (row >= n_rows) continue;
+        const long s0 = split_slot[q], s1 = split_slot[q + 1];
+        const long stride = (long)V * K;
+        const float *w = ws + (s0 * V + v) * (long)K + k;
+        float sum = 0.0f;
+        long j = s0;
+        for (; j + 8 <= s1; j += 8, w += 8 * stride) { // eight loads in flight, adds in item order
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = w[u * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += t[u];
+        }
+        for (; j < s1; ++j, w += stride) sum += w[0];
+        __builtin_nontemporal_store(sum, C + row * K + k);
+    }
+}
+
 using KernelFn = void (*)(SpmmArgs);
 
 template <int V, bool S, int LPR, int VEC> KernelFn pick_rep(int rep)
@@ -737,6 +813,19 @@ hipError_t launch_zero_panels(const int32_t *panels, int64_t n_panels, int V, fl
     if (blocks > 256 * 64) blocks = 256 * 64;
     hipLaunchKernelGGL(zero_panels_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, panels,
                        (long)n_panels, V, C, n_rows, K);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split_slot, int64_t n_split,
+                               int V, const float *ws, float *C, int32_t n_rows, int32_t K,
+                               hipStream_t stream)
+{
+    if (n_split <= 0) return hipSuccess;
+    const long total = n_split * V * (long)K;
+    long blocks = (total + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, split_panels,
+                       split_slot, (long)n_split, V, ws, C, n_rows, K);
     return hipGetLastError();
 }
 

@@ -4,6 +4,7 @@
 // share neighbours, then nodes are renumbered cluster by cluster, so rows of one cluster
 // sit next to each other and gather from a compact set of B rows.
 #include <algorithm>
+#include <atomic>
 #include <cstdint>
 #include <cstring>
 #include <new>
@@ -140,6 +141,7 @@ int pcsr_permute_csr(int64_t n, const int32_t *rowptr, const int32_t *colidx, co
             const int64_t i = inv[k];
             out_rowptr[k + 1] = out_rowptr[k] + (rowptr[i + 1] - rowptr[i]);
         }
+        std::atomic<int> bad{0};
         par_for(n, [&](int64_t lo, int64_t hi) {
             std::vector<std::pair<int32_t, float>> row;
             for (int64_t k = lo; k < hi; ++k) {
@@ -147,7 +149,10 @@ int pcsr_permute_csr(int64_t n, const int32_t *rowptr, const int32_t *colidx, co
                 const int64_t s = rowptr[i], e = rowptr[i + 1];
                 row.resize(e - s);
                 for (int64_t p = s; p < e; ++p) {
-                    if (colidx[p] < 0 || colidx[p] >= n) continue;
+                    if (colidx[p] < 0 || colidx[p] >= n) { // not a square pattern: nothing to relabel it to
+                        bad = 1;
+                        return;
+                    }
                     row[p - s] = {perm[colidx[p]], vals[p]};
                 }
                 std::sort(row.begin(), row.end(),
@@ -162,7 +167,7 @@ int pcsr_permute_csr(int64_t n, const int32_t *rowptr, const int32_t *colidx, co
                 }
             }
         });
-        return PCSR_OK;
+        return bad ? PCSR_E_BAD_CSR : PCSR_OK;
     } catch (const std::bad_alloc &) {
         return PCSR_E_OOM;
     }

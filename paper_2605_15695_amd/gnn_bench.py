@@ -28,7 +28,7 @@ def main(argv=None) -> int:
 
     import torch
 
-    from . import synth
+    import synth
     from .gnn import PcsrOperator, make_model
 
     if not torch.cuda.is_available():

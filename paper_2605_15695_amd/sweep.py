@@ -25,7 +25,7 @@ import time
 import numpy as np
 
 from . import binding as pc
-from . import synth
+import synth
 
 HBM_PEAK_GBS = 8000.0
 HIPSPARSE_ALGS = {"default": 0, "csr_alg1": 4, "csr_alg2": 6, "csr_alg3": 12}
@@ -264,7 +264,7 @@ def main(argv=None) -> int:
               f"rep={qs['rep']} gy={qs['grid_y']} waves={qs['waves_per_wg']}: {med:.4f} ms "
               f"({100 * (best_again or best[0]) / med:.1f}% of the sweep's best tuple re-timed)", flush=True)
         if not args.no_hipsparse:
-            # the paper's Algorithm 1 as printed (one wavefront per row, one column per lane)
+            # plain CSR baseline: the basic scheme of Algorithm 1 (one wavefront per row, one column per lane)
             lib = _baseline_lib()
             a1_best = None
             for W in (1, 2, 4, 8):

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import paper_2605_15695_amd as pc
-from paper_2605_15695_amd import synth
+import synth
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu

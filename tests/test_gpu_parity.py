@@ -11,7 +11,7 @@ import pytest
 import oracle
 import paper_2605_15695_amd as pc
 from oracle import pcsr_format as pf
-from paper_2605_15695_amd import synth
+import synth
 from tests.helpers import random_csr
 
 torch = pytest.importorskip("torch")
@@ -199,6 +199,18 @@ def test_column_window_edges():
     h = pc.pcsr_build(301, 200, rp, ci, va, pc.make_params(col_window=256))
     assert pc.pcsr_window_stats(h)["hit_fraction"] == 1.0
     h.close()
+    # CSR arrays in device memory: copied to the host for the window build (the caller's
+    # parameter struct is not modified by the binding)
+    prm = pc.make_params(V=2, col_window=256)
+    hd = pc.pcsr_build(301, 200, *(torch.from_numpy(x).cuda() for x in (rp, ci, va)), prm)
+    assert prm.flags == 0 and pc.pcsr_window_stats(hd)["hit_fraction"] == 1.0
+    B = synth.dense_operand(200, 16, "uniform", 16)
+    ref, bound = oracle.spmm(rp, ci, va, B)
+    Cd = torch.full((301, 16), float("nan"), dtype=torch.float32, device="cuda")
+    pc.pcsr_spmm(hd, torch.from_numpy(B).cuda(), Cd, 16)
+    torch.cuda.synchronize()
+    _check(Cd.cpu().numpy(), ref, bound, "window build from device CSR")
+    hd.close()
     with pytest.raises(pc.PcsrError):
         pc.pcsr_build(301, 200, rp, ci, va, pc.make_params(S=1, col_window=256))
     with pytest.raises(pc.PcsrError):
@@ -312,13 +324,31 @@ def test_long_row_accumulation_stays_in_tolerance():
             _check(C, ref, bound, f"long row S={S} {kern}")
 
 
+_FULL = {}
+
+
+def _full_graph(name):
+    """Full-size workloads are generated once per test process (rmat22 takes about a minute)."""
+    if name not in _FULL:
+        _FULL.clear()                            # keep at most one: rmat22 alone holds 1.5 GB
+        _FULL[name] = synth.workload(name, "full")
+    return _FULL[name]
+
+
+def _sample_rows(g, n_random=20000):
+    rng = np.random.default_rng(0)
+    deg = g.degrees()
+    return np.unique(np.concatenate([rng.integers(0, g.n_rows, n_random), [0, g.n_rows - 1],
+                                     np.argsort(deg)[-50:], np.nonzero(deg == 0)[0][:50]]))
+
+
 @pytest.mark.parametrize("name,K", [("road", 128), ("rmat20", 64), ("sbm", 256), ("sbm_shuffled", 256),
                                     ("rmat22", 32)])
 def test_full_size_sampled_rows(name, K):
     """Every benchmark workload at full size in the launch configuration bench.py times
     (the library's own pick); the oracle recomputes a sample of rows one by one, the
     longest rows and some empty ones included."""
-    g = synth.workload(name, "full")
+    g = _full_graph(name)
     B = synth.dense_operand(g.n_cols, K, synth.WORKLOADS[name]["B"], 2)
     sel = pc.pcsr_select(pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx), K)
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, sel)
@@ -327,16 +357,152 @@ def test_full_size_sampled_rows(name, K):
     Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
     pc.pcsr_spmm(h, Bd, Cd, K)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(0)
-    deg = g.degrees()
-    rows = np.unique(np.concatenate([rng.integers(0, g.n_rows, 20000), [0, g.n_rows - 1],
-                                     np.argsort(deg)[-50:], np.nonzero(deg == 0)[0][:50]]))
+    rows = _sample_rows(g)
     ref, bound = oracle.spmm_rows(g.rowptr, g.colidx, g.vals, B, rows)
     got = Cd[torch.from_numpy(rows).cuda()].cpu().numpy()
     _check(got, ref, bound, f"{name} full sampled")
     # property that holds at any size: nothing left unwritten
     assert not torch.isnan(Cd).any().item()
     h.close()
+
+
+@pytest.mark.parametrize("K", [256, 512])
+def test_largest_workload_where_offsets_need_64_bits(K):
+    """R-MAT scale 22 at the widths where B and C pass 2^32 bytes (K = 256) and 2^31 elements
+    (K = 512): the library's own pick (the configuration bench.py times), the tuple the
+    recorded sweeps rank first there (V=2, S=1, SG=1024), the same with the atomic
+    write-back, and an unsplit V=1 tuple, each against oracle rows that include the
+    162K-nonzero rows, the last row and 6000 random ones.  The balanced results must also
+    be the same bits on a second run."""
+    g = _full_graph("rmat22")
+    assert g.n_rows * K * 4 >= 2**32
+    B = synth.dense_operand(g.n_cols, K, "normal", 2)
+    rows = _sample_rows(g, 6000)
+    assert rows[-1] == g.n_rows - 1 and int(rows[-1]) * K * 4 >= 2**32 - 4 * K
+    if K == 512:
+        assert (rows.astype(np.int64) * K >= 2**31).sum() > 1000      # element offsets past int32
+    ref, bound = oracle.spmm_rows(g.rowptr, g.colidx, g.vals, B, rows)
+    Bd = torch.from_numpy(B).cuda()
+    del B
+    rows_d = torch.from_numpy(rows).cuda()
+    Cd = torch.empty((g.n_rows, K), dtype=torch.float32, device="cuda")
+    sel = pc.pcsr_select(pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx), K)
+    tuples = [("selected", sel, 0),
+              ("V=2 S=1 SG=1024", pc.make_params(V=2, S=1, SG=1024, lanes_per_row=16, vec=4, rep=1, waves_per_wg=2), 0),
+              ("V=2 S=1 SG=1024 atomic", None, pc.PCSR_FLAG_ATOMIC_SPLIT),
+              ("V=1 S=0", pc.make_params(V=1, S=0, lanes_per_row=64, vec=4, rep=K // 256, waves_per_wg=4), 0)]
+    h = None
+    for what, params, kflags in tuples:
+        if params is not None:
+            if h is not None:
+                h.close()
+            h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, params)
+        else:
+            pc.pcsr_set_kernel_params(h, 16, 4, 1, 2, 0, kflags)
+        print(f"case rmat22 K={K} {what} {pc.pcsr_query_launch(h, K)}", flush=True)
+        Cd.fill_(float("nan"))
+        pc.pcsr_spmm(h, Bd, Cd, K)
+        torch.cuda.synchronize()
+        got = Cd[rows_d].cpu().numpy()
+        _check(got, ref, bound, f"rmat22 K={K} {what}")
+        assert not torch.isnan(Cd).any().item()
+        if not kflags:
+            first = Cd[rows_d].clone()
+            tail = Cd[-4096:].clone()
+            Cd.fill_(1e30)
+            pc.pcsr_spmm(h, Bd, Cd, K)
+            torch.cuda.synchronize()
+            assert torch.equal(first.view(torch.int32), Cd[rows_d].view(torch.int32)), what
+            assert torch.equal(tail.view(torch.int32), Cd[-4096:].view(torch.int32)), what
+    h.close()
+
+
+@pytest.mark.parametrize("name", ["rmat20", "rmat22", "sbm"])
+@pytest.mark.parametrize("V", [1, 2])
+def test_balanced_write_back_is_deterministic_and_needs_no_clean_output(name, V):
+    """S = 1 without atomics: two runs over outputs prefilled with different garbage give
+    identical bits; the handle built by GPU kernels gives the same bits as the host-built one;
+    the atomic write-back stays within tolerance of the oracle."""
+    g = _graph(name)
+    K = 48
+    B, ref, bound = _oracle(name, g, K, synth.WORKLOADS[name]["B"])
+    Bd = torch.from_numpy(B).cuda()
+    outs = []
+    for flags in (0, pc.PCSR_FLAG_GPU_BUILD):
+        h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=1, SG=8, flags=flags))
+        e = pc.pcsr_export(h)
+        n_items = int(np.sum(np.bincount(e["trow"], minlength=e["P"])[np.bincount(e["trow"], minlength=e["P"]) > 1]))
+        assert pc.pcsr_workspace_bytes(h, K) == n_items * V * K * 4
+        for fill in (float("nan"), 1e30):
+            Cd = torch.full((g.n_rows, K), fill, dtype=torch.float32, device="cuda")
+            pc.pcsr_spmm(h, Bd, Cd, K)
+            torch.cuda.synchronize()
+            outs.append(Cd.cpu().numpy())
+        pc.pcsr_set_kernel_params(h, flags=pc.PCSR_FLAG_ATOMIC_SPLIT)
+        assert pc.pcsr_workspace_bytes(h, K) == 0
+        Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+        pc.pcsr_spmm(h, Bd, Cd, K)
+        torch.cuda.synchronize()
+        _check(Cd.cpu().numpy(), ref, bound, f"{name} V={V} atomic write-back")
+        h.close()
+    _check(outs[0], ref, bound, f"{name} V={V} two-pass write-back")
+    for o in outs[1:]:
+        assert np.array_equal(outs[0].view(np.uint32), o.view(np.uint32))
+
+
+def test_workspace_grows_with_k_and_can_be_reserved_before_capture():
+    g = _graph("rmat20")
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=1, S=1, SG=16))
+    assert pc.pcsr_workspace_bytes(h, 64) == 4 * pc.pcsr_workspace_bytes(h, 16) > 0
+    for K in (16, 64, 32):                       # grows once, then shrinking K reuses the block
+        B, ref, bound = _oracle("rmat20", g, K, "normal")
+        Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+        pc.pcsr_spmm(h, torch.from_numpy(B).cuda(), Cd, K)
+        torch.cuda.synchronize()
+        _check(Cd.cpu().numpy(), ref, bound, f"workspace K={K}")
+    K = 128
+    B, ref, bound = _oracle("rmat20", g, K, "normal")
+    Bd = torch.from_numpy(B).cuda()
+    Cd = torch.zeros((g.n_rows, K), dtype=torch.float32, device="cuda")
+    pc.pcsr_reserve_workspace(h, K)              # instead of a warm-up call outside the capture
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pc.pcsr_spmm(h, Bd, Cd, K, torch.cuda.current_stream())
+    outs = []
+    for replay in range(3):
+        Cd.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        outs.append(Cd.clone())
+        _check(Cd.cpu().numpy(), ref, bound, f"captured S=1 replay {replay}")
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    h.close()
+    h0 = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=2, S=0))
+    assert pc.pcsr_workspace_bytes(h0, 64) == 0
+    h0.close()
+
+
+def test_non_finite_b_row_stays_in_the_rows_that_reference_it():
+    """A B row of +Inf may only reach the C rows whose A row has that column (V = 1: the
+    format adds no padding): the batched walk must select, not multiply by zero."""
+    g = _graph("road")
+    K = 32
+    B = synth.dense_operand(g.n_cols, K, "normal", 9).copy()
+    bad_col = int(g.colidx[g.rowptr[g.n_rows // 2]])
+    B[bad_col] = np.inf
+    touched = np.zeros(g.n_rows, bool)
+    touched[np.repeat(np.arange(g.n_rows), g.degrees())[g.colidx == bad_col]] = True
+    ref, bound = oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+    assert np.isfinite(ref[~touched]).all() and not np.isfinite(ref[touched]).any()
+    for kern in [(8, 4, 1, 2, 1), (8, 4, 1, 2, 2), (8, 4, 1, 2, 4), (16, 2, 1, 4, 4), (64, 1, 1, 1, 2)]:
+        C = _spmm(g, B, pc.make_params(V=1, S=0), K, kernel=kern)
+        assert np.isfinite(C[~touched]).all(), kern
+        assert np.isposinf(ref[touched]).all() and np.isposinf(C[touched]).all(), kern
+        ok, worst = oracle.within_tolerance(C[~touched], ref[~touched], bound[~touched], RTOL, ATOL)
+        assert ok, (kern, worst)
 
 
 @pytest.mark.parametrize("K", [48, 80, 96, 112, 144, 160, 176, 208, 240])
@@ -537,17 +703,26 @@ def test_seeded_random_configurations():
         flags = pc.PCSR_FLAG_NO_XCD_REMAP if rng.random() < 0.3 else 0
         if rng.random() < 0.3 and not cw:
             flags |= pc.PCSR_FLAG_GPU_BUILD
+        if S and rng.random() < 0.4:
+            flags |= pc.PCSR_FLAG_ATOMIC_SPLIT
         what = (f"case {case}: {n_rows}x{n_cols} d={density} K={K} V={V} S={S} SG={SG} cw={cw} "
                 f"lpr={lpr} vec={vec} rep={rep} waves={waves} ipg={ipg} flags={flags}")
         print(what, flush=True)
         g = synth.Graph("rnd", n_rows, n_cols, rp, ci, va)
         h = pc.pcsr_build(n_rows, n_cols, rp, ci, va, pc.make_params(V=V, S=S, SG=SG, col_window=cw, flags=flags))
-        pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, ipg, flags & pc.PCSR_FLAG_NO_XCD_REMAP)
+        pc.pcsr_set_kernel_params(h, lpr, vec, rep, waves, ipg,
+                                  flags & (pc.PCSR_FLAG_NO_XCD_REMAP | pc.PCSR_FLAG_ATOMIC_SPLIT))
+        # the refusals pcsr.h documents: items_per_group needs ipg < lanes and V*vec*rep*ipg <= 32,
+        # the column window needs col_window rows of (lanes*vec*rep + 4) floats within 160 KiB of LDS
+        refuse = (ipg > 1 and not (ipg < lpr and V * vec * rep * ipg <= 32)) or \
+                 (cw > 0 and cw * (lpr * vec * rep + 4) * 4 > 160 * 1024)
         try:
             q = pc.pcsr_query_launch(h, K)
-        except pc.PcsrError:
+        except pc.PcsrError as e:
+            assert refuse and e.code == pc.binding.PCSR_E_UNSUPPORTED, what
             h.close()
-            continue                              # combination the library documents as unsupported
+            continue
+        assert not refuse, what
         if q["grid_y"] > 64:
             h.close()
             continue

@@ -9,7 +9,8 @@ import pytest
 
 import paper_2605_15695_amd as pc
 from oracle import pcsr_format as pf
-from paper_2605_15695_amd import binding, synth
+import synth
+from paper_2605_15695_amd import binding
 from tests.helpers import random_csr
 
 ROOT = pathlib.Path(__file__).resolve().parent.parent
@@ -204,6 +205,33 @@ def test_reorder_error_paths_and_degenerate_inputs():
     with pytest.raises(pc.PcsrError):
         pc.pcsr_permute_csr(2, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32),
                             np.ones(2, np.float32), np.array([0, 0], np.int32))
+    # a column outside [0, n) cannot be relabelled: an error, not a silently wrong row
+    for bad in (5, -1):
+        with pytest.raises(pc.PcsrError) as ei:
+            pc.pcsr_permute_csr(2, np.array([0, 1, 2], np.int32), np.array([0, bad], np.int32),
+                                np.ones(2, np.float32), np.array([1, 0], np.int32))
+        assert ei.value.code == binding.PCSR_E_BAD_CSR
+
+
+def test_workspace_size_of_the_balanced_write_back():
+    """V*K floats per work item of every panel that was split; nothing without balancing or
+    with the atomic write-back."""
+    g = synth.workload("rmat20", "small")
+    for V in (1, 2):
+        h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=1, SG=16, flags=HOST))
+        r = pf.pcsr_ref(g.n_rows, g.rowptr, g.colidx, g.vals, V, 1, 16, 64)
+        per_panel = np.bincount(r["trow"], minlength=r["P"])
+        slots = int(per_panel[per_panel > 1].sum())
+        assert slots > 0
+        assert pc.pcsr_workspace_bytes(h, 40) == slots * V * 40 * 4
+        pc.pcsr_set_kernel_params(h, flags=pc.PCSR_FLAG_ATOMIC_SPLIT)
+        assert pc.pcsr_workspace_bytes(h, 40) == 0
+        with pytest.raises(pc.PcsrError):
+            pc.pcsr_reserve_workspace(h, 40)              # host-only handle: nothing to reserve on
+        h.close()
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=1, S=0, flags=HOST))
+    assert pc.pcsr_workspace_bytes(h, 40) == 0
+    h.close()
 
 
 def test_transpose_csr_host():

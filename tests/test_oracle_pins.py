@@ -8,7 +8,7 @@ import pytest
 import scipy.sparse as sp
 
 import oracle
-from paper_2605_15695_amd import synth
+import synth
 from tests.helpers import dense_to_csr, random_csr
 
 

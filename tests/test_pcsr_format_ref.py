@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import pcsr_format as pf
-from paper_2605_15695_amd import synth
+import synth
 from tests.helpers import random_csr
 
 GOLDEN = pathlib.Path(__file__).parent / "golden"
