@@ -368,8 +368,8 @@ def test_full_size_sampled_rows(name, K):
 
 @pytest.mark.parametrize("K", [256, 512])
 def test_largest_workload_where_offsets_need_64_bits(K):
-    """R-MAT scale 22 at the widths where B and C pass 2^32 bytes (K = 256) and 2^31 elements
-    (K = 512): the library's own pick (the configuration bench.py times), the tuple the
+    """R-MAT scale 22 at the widths where B and C reach 2^32 bytes (K = 256) and 2^33 bytes, 2^31
+    elements (K = 512): the library's own pick (the configuration bench.py times), the tuple the
     recorded sweeps rank first there (V=2, S=1, SG=1024), the same with the atomic
     write-back, and an unsplit V=1 tuple, each against oracle rows that include the
     162K-nonzero rows, the last row and 6000 random ones.  The balanced results must also
@@ -378,9 +378,10 @@ def test_largest_workload_where_offsets_need_64_bits(K):
     assert g.n_rows * K * 4 >= 2**32
     B = synth.dense_operand(g.n_cols, K, "normal", 2)
     rows = _sample_rows(g, 6000)
-    assert rows[-1] == g.n_rows - 1 and int(rows[-1]) * K * 4 >= 2**32 - 4 * K
-    if K == 512:
-        assert (rows.astype(np.int64) * K >= 2**31).sum() > 1000      # element offsets past int32
+    assert rows[-1] == g.n_rows - 1
+    # many sampled rows start past 2^31 bytes (K = 256: signed 32-bit byte offsets would wrap) or
+    # past 2^32 bytes (K = 512: unsigned ones would too; the last element index is 2^31 - 1)
+    assert (rows.astype(np.int64) * K * 4 >= (2**31 if K == 256 else 2**32)).sum() > 1000
     ref, bound = oracle.spmm_rows(g.rowptr, g.colidx, g.vals, B, rows)
     Bd = torch.from_numpy(B).cuda()
     del B
