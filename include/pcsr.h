@@ -28,7 +28,8 @@ enum {
                                 column out of range, columns of a row not strictly ascending  */
     PCSR_E_UNSUPPORTED = -3, /* V not in {1,2}, K <= 0, vec does not divide K, bad kernel
                                 parameter, SpMM on a host-only handle                        */
-    PCSR_E_TOO_LARGE = -4,   /* nnz, n_rows or the item count does not fit int32             */
+    PCSR_E_TOO_LARGE = -4,   /* nnz, n_rows or the item count does not fit int32; workspace
+                                need beyond the fixed block of pcsr_spmm_static             */
     PCSR_E_OOM = -5,         /* host or device allocation failed                             */
     PCSR_E_HIP = -6          /* a HIP runtime call failed (see pcsr_last_hip_error)          */
 };
@@ -138,6 +139,23 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
  * device than the current one), UNSUPPORTED, OOM, HIP.
  */
 int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream);
+
+/*
+ * pcsr_spmm for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results, but the workspace of the balanced write-back is a
+ * fixed block of pcsr_static_scratch_bytes() bytes (64 MiB) inside the library's device
+ * image, one per GPU, held until the process ends; the call never allocates or frees.
+ * A call whose workspace need (pcsr_workspace_bytes) exceeds that block returns
+ * PCSR_E_TOO_LARGE and enqueues nothing.  Every call on a GPU, from any handle, shares
+ * that GPU's block: calls that overlap in time on one GPU (two streams, two threads)
+ * race; serialise them.  Nothing in the block has to be cleared between calls (every
+ * slot that is read was written earlier in the same call).  The first call on a device
+ * looks the block's address up and should be made outside stream capture.
+ * Errors: as pcsr_spmm, plus TOO_LARGE; never OOM.
+ */
+int pcsr_spmm_static(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream);
+int64_t pcsr_static_scratch_bytes(void);
 
 /*
  * Workspace of the balanced write-back (see pcsr_spmm): bytes an SpMM of width K needs

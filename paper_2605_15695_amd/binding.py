@@ -56,6 +56,8 @@ def _lib():
         lib.pcsr_build.argtypes = [i64, i64, i64, vp, vp, vp, pp, ctypes.POINTER(vp)]
         lib.pcsr_spmm.argtypes = [vp, vp, vp, i32, vp]
         lib.pcsr_free.argtypes = [vp]
+        lib.pcsr_spmm_static.argtypes = [vp, vp, vp, i32, vp]
+        lib.pcsr_static_scratch_bytes.restype = i64
         lib.pcsr_workspace_bytes.argtypes = [vp, i32, ctypes.POINTER(i64)]
         lib.pcsr_reserve_workspace.argtypes = [vp, i32]
         lib.pcsr_set_kernel_params.argtypes = [vp, i32, i32, i32, i32, i32, i32]
@@ -76,7 +78,7 @@ def _lib():
         for name in ("pcsr_build", "pcsr_spmm", "pcsr_free", "pcsr_set_kernel_params",
                      "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select",
                      "pcsr_window_stats", "pcsr_features_device", "pcsr_reorder", "pcsr_permute_csr",
-                     "pcsr_transpose_csr", "pcsr_workspace_bytes", "pcsr_reserve_workspace"):
+                     "pcsr_transpose_csr", "pcsr_workspace_bytes", "pcsr_reserve_workspace", "pcsr_spmm_static"):
             getattr(lib, name).restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -176,6 +178,24 @@ def pcsr_reserve_workspace(h: Handle, K: int) -> None:
     rc = _lib().pcsr_reserve_workspace(h.raw, K)
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_reserve_workspace")
+
+
+def pcsr_spmm_static(h: Handle, B, C, K: int, stream=None) -> None:
+    """pcsr_spmm with the library's fixed workspace: allocates nothing."""
+    _, p_b, dev_b = _ptr(B, np.dtype(np.float32))
+    _, p_c, dev_c = _ptr(C, np.dtype(np.float32))
+    if not (dev_b and dev_c):
+        raise ValueError("B and C must be device tensors")
+    if B.numel() != h.n_cols * K or C.numel() != h.n_rows * K:
+        raise ValueError("B must be n_cols x K and C n_rows x K")
+    s = getattr(stream, "cuda_stream", stream)
+    rc = _lib().pcsr_spmm_static(h.raw, p_b, p_c, K, s)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_spmm_static")
+
+
+def pcsr_static_scratch_bytes() -> int:
+    return int(_lib().pcsr_static_scratch_bytes())
 
 
 def pcsr_free(h: Handle) -> None:

@@ -477,6 +477,20 @@ int pcsr_spmm(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream
     return spmm_enqueue(h, B, C, K, ls, h->d_ws, static_cast<hipStream_t>(stream));
 }
 
+int pcsr_spmm_static(pcsr_handle_t h, const float *B, float *C, int32_t K, void *stream)
+{
+    pcsr::LaunchShape ls;
+    int rc = spmm_check(h, B, C, K, &ls);
+    if (rc != PCSR_OK) return rc;
+    if (h->host.n_rows == 0) return PCSR_OK;
+    if (workspace_need(h, K) > (int64_t)pcsr::kStaticScratchBytes) return PCSR_E_TOO_LARGE;
+    void *ws = nullptr;
+    if (!hip_ok(pcsr::static_scratch(&ws))) return PCSR_E_HIP;
+    return spmm_enqueue(h, B, C, K, ls, static_cast<float *>(ws), static_cast<hipStream_t>(stream));
+}
+
+int64_t pcsr_static_scratch_bytes(void) { return (int64_t)pcsr::kStaticScratchBytes; }
+
 int pcsr_workspace_bytes(pcsr_handle_t h, int32_t K, int64_t *bytes)
 {
     if (!valid(h) || !bytes) return PCSR_E_INVALID_ARG;
@@ -669,7 +683,7 @@ const char *pcsr_strerror(int code)
     case PCSR_E_INVALID_ARG: return "invalid argument";
     case PCSR_E_BAD_CSR: return "malformed CSR (rowptr not monotone, column out of range, unsorted or duplicate columns)";
     case PCSR_E_UNSUPPORTED: return "unsupported parameter value";
-    case PCSR_E_TOO_LARGE: return "size does not fit 32-bit indexing";
+    case PCSR_E_TOO_LARGE: return "size does not fit 32-bit indexing, or the fixed workspace";
     case PCSR_E_OOM: return "out of memory";
     case PCSR_E_HIP: return "HIP runtime error";
     }

@@ -61,4 +61,10 @@ hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split
                                int V, const float *ws, float *C, int32_t n_rows, int32_t K,
                                hipStream_t stream);
 
+// Fixed workspace for callers that cannot allocate: one block of kStaticScratchBytes
+// bytes per GPU, part of the library's device image and held until the process ends.
+// static_scratch returns its address on the current device (looked up once per device).
+constexpr size_t kStaticScratchBytes = size_t(64) << 20;
+hipError_t static_scratch(void **ptr);
+
 } // namespace pcsr

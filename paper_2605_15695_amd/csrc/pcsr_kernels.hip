@@ -16,6 +16,8 @@
 // logarithmic-ish on rows with 1e5 nonzeros.
 #include "pcsr_kernels.h"
 
+#include <mutex>
+
 // registers of B data a lane keeps in flight per gather step
 #ifndef PCSR_INFLIGHT
 #define PCSR_INFLIGHT 16
@@ -27,6 +29,10 @@
 #ifndef PCSR_MAXSTEP
 #define PCSR_MAXSTEP 8
 #endif
+
+// Workspace of the entry point that allocates nothing (pcsr_spmm_static).  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels get the looked-up address.
+static __device__ __align__(256) unsigned char scratch[pcsr::kStaticScratchBytes];
 
 namespace pcsr {
 namespace {
@@ -814,6 +820,28 @@ hipError_t launch_zero_panels(const int32_t *panels, int64_t n_panels, int V, fl
     hipLaunchKernelGGL(zero_panels_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, panels,
                        (long)n_panels, V, C, n_rows, K);
     return hipGetLastError();
+}
+
+hipError_t static_scratch(void **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *addr[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        // every GPU holds its own copy of the array at its own address
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split_slot, int64_t n_split,

@@ -30,7 +30,7 @@ def _assert_same(e, r):
 
 def test_every_declared_symbol_is_exported():
     header = (ROOT / "include" / "pcsr.h").read_text()
-    names = set(re.findall(r"^(?:int|int32_t|const char \*)\s*(pcsr_[a-z_]+)\(", header, re.M))
+    names = set(re.findall(r"^(?:int|int32_t|int64_t|const char \*)\s*(pcsr_[a-z_]+)\(", header, re.M))
     assert len(names) >= 11
     assert {"pcsr_build", "pcsr_spmm", "pcsr_free"} <= names
     lib = ctypes.CDLL(str(binding.LIB_PATH))
