@@ -45,6 +45,12 @@ enum {
                                   always built this way.  With col_window the flag is ignored:
                                   windows are chosen on the host, and CSR arrays given in
                                   device memory are copied to the host for that build        */
+    PCSR_FLAG_COLUMN_ORDER = 64,/* S = 1 only: column-ordered schedule.  The work items of
+                                  panels that were split run in ascending order of their first
+                                  column, dealt to the 8 XCDs as 8 contiguous column ranges,
+                                  so that the wavefronts of one XCD gather the same rows of B
+                                  at about the same time; all other items run in index order.
+                                  The PCSR arrays do not change.  Built on the host            */
     PCSR_FLAG_ATOMIC_SPLIT = 32 /* S = 1 only: panels that were split accumulate into C with
                                   fp32 atomics, as Algorithm 2 prints it, instead of the
                                   default two-pass write-back (see pcsr_spmm)                 */

@@ -19,6 +19,7 @@ PCSR_E_TOO_LARGE, PCSR_E_OOM, PCSR_E_HIP = -4, -5, -6
 PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_NO_VALIDATE, PCSR_FLAG_NO_XCD_REMAP, PCSR_FLAG_HOST_ONLY = 1, 2, 4, 8
 PCSR_FLAG_GPU_BUILD = 16
 PCSR_FLAG_ATOMIC_SPLIT = 32
+PCSR_FLAG_COLUMN_ORDER = 64
 PCSR_N_FEATURES = 16
 FEATURE_NAMES = ("n", "n_hat", "nnz", "delta", "d", "d_hat", "d_max", "CV", "CV_hat",
                  "SR_1", "SR_2", "rho", "b", "b_max", "PR_1", "PR_2")

@@ -51,7 +51,8 @@ struct pcsr_handle_s {
     float *d_val = nullptr;
     int32_t *d_trow = nullptr;
     int32_t *d_split = nullptr;       // panels that own more than one item, ascending
-    int32_t *d_split_first = nullptr; // their first items
+    int32_t *d_item_slot = nullptr;   // per item: workspace slot, -1 for a sole item (S only)
+    int32_t *d_sched = nullptr;       // column-ordered schedule: 4 int32 per launch position
     int32_t *d_split_slot = nullptr;  // their first workspace slots (n_split + 1 entries)
     int32_t *d_win = nullptr;
     int64_t n_split = 0;
@@ -72,12 +73,13 @@ void release_device(pcsr_handle_t h)
     if (h->d_val) (void)hipFree(h->d_val);
     if (h->d_trow) (void)hipFree(h->d_trow);
     if (h->d_split) (void)hipFree(h->d_split);
-    if (h->d_split_first) (void)hipFree(h->d_split_first);
+    if (h->d_item_slot) (void)hipFree(h->d_item_slot);
+    if (h->d_sched) (void)hipFree(h->d_sched);
     if (h->d_split_slot) (void)hipFree(h->d_split_slot);
     if (h->d_win) (void)hipFree(h->d_win);
     if (h->d_ws) (void)hipFree(h->d_ws);
     h->d_rowptr = h->d_colidx = h->d_trow = h->d_split = h->d_win = nullptr;
-    h->d_split_first = h->d_split_slot = nullptr;
+    h->d_item_slot = h->d_sched = h->d_split_slot = nullptr;
     h->d_val = h->d_ws = nullptr;
     h->ws_bytes = 0;
 }
@@ -200,7 +202,9 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     if (host_only && (prm.flags & PCSR_FLAG_DEVICE_CSR)) return PCSR_E_INVALID_ARG;
 
     const bool device_csr = (prm.flags & PCSR_FLAG_DEVICE_CSR) != 0;
-    if ((device_csr || (prm.flags & PCSR_FLAG_GPU_BUILD)) && !prm.col_window) {
+    const bool column_order = (prm.flags & PCSR_FLAG_COLUMN_ORDER) != 0;
+    if (column_order && (!prm.S || prm.col_window)) return PCSR_E_UNSUPPORTED;
+    if ((device_csr || (prm.flags & PCSR_FLAG_GPU_BUILD)) && !prm.col_window && !column_order) {
         if (host_only) return PCSR_E_INVALID_ARG;
         // ---- PCSR generation on the GPU
         int32_t *t_rowptr = nullptr, *t_colidx = nullptr;
@@ -242,7 +246,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             (void)hipFree(db.val);
             if (db.trow) (void)hipFree(db.trow);
             if (db.split) (void)hipFree(db.split);
-            if (db.split_first) (void)hipFree(db.split_first);
+            if (db.item_slot) (void)hipFree(db.item_slot);
             if (db.split_slot) (void)hipFree(db.split_slot);
             return PCSR_E_OOM;
         }
@@ -262,7 +266,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         h->d_val = db.val;
         h->d_trow = db.trow;
         h->d_split = db.split;
-        h->d_split_first = db.split_first;
+        h->d_item_slot = db.item_slot;
         h->d_split_slot = db.split_slot;
         h->n_split = db.n_split;
         h->n_split_items = db.n_split_items;
@@ -282,8 +286,9 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     }
 
     try {
-        // The column-window build runs on the host: CSR arrays handed over in device memory
-        // are copied there first (every other device-CSR build took the GPU branch above).
+        // The column-window build and the column-ordered schedule run on the host: CSR arrays
+        // handed over in device memory are copied there first (every other device-CSR build
+        // took the GPU branch above).
         std::vector<int32_t> s_rowptr, s_colidx;
         std::vector<float> s_vals;
         if (device_csr) {
@@ -314,6 +319,13 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             delete h;
             return rc;
         }
+        if (column_order) {
+            rc = pcsr::schedule_by_column(&h->host);
+            if (rc != PCSR_OK) {
+                delete h;
+                return rc;
+            }
+        }
         if (prm.col_window) {
             rc = pcsr::choose_windows(&h->host, prm.col_window);
             if (rc != PCSR_OK) {
@@ -340,7 +352,8 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             if (rc == PCSR_OK) rc = upload(h->host.val, &h->d_val);
             if (rc == PCSR_OK && h->host.S) rc = upload(h->host.trow, &h->d_trow);
             if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_panels, &h->d_split);
-            if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_first, &h->d_split_first);
+            if (rc == PCSR_OK && h->host.S) rc = upload(h->host.item_slot, &h->d_item_slot);
+            if (rc == PCSR_OK && !h->host.sched.empty()) rc = upload(h->host.sched, &h->d_sched);
             if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_slot, &h->d_split_slot);
             if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_start, &h->d_win);
             if (rc != PCSR_OK) {
@@ -354,7 +367,8 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             std::vector<float>().swap(h->host.val);
             std::vector<int32_t>().swap(h->host.trow);
             std::vector<int32_t>().swap(h->host.split_panels);
-            std::vector<int32_t>().swap(h->host.split_first);
+            std::vector<int32_t>().swap(h->host.item_slot);
+            std::vector<int32_t>().swap(h->host.sched);
             std::vector<int32_t>().swap(h->host.split_slot);
             std::vector<int32_t>().swap(h->host.win_start);
         }
@@ -424,10 +438,8 @@ static int spmm_enqueue(pcsr_handle_t h, const float *B, float *C, int32_t K, co
     a.xcd_remap = (h->flags & PCSR_FLAG_NO_XCD_REMAP) ? 0 : 1;
     for (int x = 0; x < 9; ++x) a.xb[x] = h->host.xcd_bounds[x];
     a.ws = two_pass ? ws : nullptr;
-    a.split_panels = h->d_split;
-    a.split_first = h->d_split_first;
-    a.split_slot = h->d_split_slot;
-    a.n_split = (int32_t)h->n_split;
+    a.item_slot = h->d_item_slot;
+    a.sched = reinterpret_cast<const int4 *>(h->d_sched);
     a.win_start = h->d_win;
     a.win_cols = h->host.win_cols;
     a.win_items = h->host.win_items;

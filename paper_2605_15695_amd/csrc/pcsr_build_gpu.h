@@ -11,7 +11,7 @@ struct DeviceBuild {
     float *val = nullptr;      // nnz_v * V
     int32_t *trow = nullptr;   // M (S only)
     int32_t *split = nullptr;  // panels with more than one item (S only), ascending, n_split entries
-    int32_t *split_first = nullptr; // first item of each of them, n_split entries
+    int32_t *item_slot = nullptr;   // per item (S only): workspace slot, -1 for a sole item
     int32_t *split_slot = nullptr;  // first workspace slot of each of them, n_split + 1 entries
     int64_t P = 0, M = 0, nnz_v = 0, n_split = 0, n_split_items = 0, max_item_len = 0;
     int32_t SG = 0;

@@ -117,22 +117,6 @@ __global__ void items_kernel(int64_t P, const int32_t *prow, int32_t sg, int32_t
     items[p] = it > 1 ? it : 1;
 }
 
-// rewritten rowPtr and TRow
-__global__ void split_fill_kernel(int64_t P, const int32_t *prow, const int32_t *first, int32_t sg,
-                                  int32_t *out_rowptr, int32_t *out_trow)
-{
-    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= P) return;
-    int64_t start = prow[p];
-    const int i0 = first[p], i1 = first[p + 1];
-    for (int it = i0; it < i1; ++it) {
-        out_rowptr[it] = (int32_t)start;
-        out_trow[it] = (int32_t)p;
-        start += sg;
-    }
-    if (p == P - 1) out_rowptr[i1] = prow[P];
-}
-
 // Panels that own more than one item, in ascending order (positions come from scans, so
 // the tables are the same on every run): mark[p] = 1 and cnt[p] = items for such a panel.
 __global__ void split_marks_kernel(int64_t P, const int32_t *items, int32_t *mark, int32_t *cnt)
@@ -144,10 +128,30 @@ __global__ void split_marks_kernel(int64_t P, const int32_t *items, int32_t *mar
     cnt[p] = it > 1 ? it : 0;
 }
 
+// rewritten rowPtr, TRow and the workspace slot of every item (first / slotbase: exclusive
+// scans of items / cnt)
+__global__ void split_fill_kernel(int64_t P, const int32_t *prow, const int32_t *first,
+                                  const int32_t *slotbase, int32_t sg, int32_t *out_rowptr,
+                                  int32_t *out_trow, int32_t *out_slot)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    int64_t start = prow[p];
+    const int i0 = first[p], i1 = first[p + 1];
+    int slot = i1 - i0 > 1 ? slotbase[p] : -1;
+    for (int it = i0; it < i1; ++it) {
+        out_rowptr[it] = (int32_t)start;
+        out_trow[it] = (int32_t)p;
+        out_slot[it] = slot;
+        if (slot >= 0) ++slot;
+        start += sg;
+    }
+    if (p == P - 1) out_rowptr[i1] = prow[P];
+}
+
 // qpos / slotbase: exclusive scans of mark / cnt over P + 1 entries
-__global__ void split_tables_kernel(int64_t P, const int32_t *items, const int32_t *first, const int32_t *qpos,
-                                    const int32_t *slotbase, int32_t *split_panels, int32_t *split_first,
-                                    int32_t *split_slot)
+__global__ void split_tables_kernel(int64_t P, const int32_t *items, const int32_t *qpos,
+                                    const int32_t *slotbase, int32_t *split_panels, int32_t *split_slot)
 {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (p > P) return;
@@ -158,7 +162,6 @@ __global__ void split_tables_kernel(int64_t P, const int32_t *items, const int32
     if (items[p] > 1) {
         const int q = qpos[p];
         split_panels[q] = (int32_t)p;
-        split_first[q] = first[p];
         split_slot[q] = slotbase[p];
     }
 }
@@ -430,7 +433,7 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
     out->n_split_items = 0;
     out->trow = nullptr;
     out->split = nullptr;
-    out->split_first = nullptr;
+    out->item_slot = nullptr;
     out->split_slot = nullptr;
 
     int32_t *final_rowptr = prow;
@@ -449,17 +452,7 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
         int32_t m32 = 0;
         HIP_TRY(hipMemcpy(&m32, first + P, sizeof(int32_t), hipMemcpyDeviceToHost));
         M = m32;
-        int32_t *srow = nullptr, *trow = nullptr;
-        HIP_TRY(sc.alloc((void **)&srow, sizeof(int32_t) * (M + 1)));
-        HIP_TRY(sc.alloc((void **)&trow, sizeof(int32_t) * (M + 1)));
-        if (P > 0) {
-            hipLaunchKernelGGL(split_fill_kernel, dim3(blocks_for(P)), dim3(kThreads), 0, 0, P, prow, first,
-                               (int32_t)sg, srow, trow);
-            HIP_TRY(hipGetLastError());
-        } else {
-            HIP_TRY(hipMemset(srow, 0, sizeof(int32_t)));
-        }
-        // tables of the split panels: panel, first item, first workspace slot
+        // panels that were split: ascending list, first workspace slot of each
         int32_t *mark = nullptr, *cnt = nullptr, *qpos = nullptr, *slotbase = nullptr;
         HIP_TRY(sc.alloc((void **)&mark, sizeof(int32_t) * (P + 1)));
         HIP_TRY(sc.alloc((void **)&cnt, sizeof(int32_t) * (P + 1)));
@@ -473,23 +466,34 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
         int32_t n_split = 0, n_split_items = 0;
         HIP_TRY(hipMemcpy(&n_split, qpos + P, sizeof(int32_t), hipMemcpyDeviceToHost));
         HIP_TRY(hipMemcpy(&n_split_items, slotbase + P, sizeof(int32_t), hipMemcpyDeviceToHost));
-        int32_t *split = nullptr, *split_first = nullptr, *split_slot = nullptr;
+
+        int32_t *srow = nullptr, *trow = nullptr, *item_slot = nullptr;
+        HIP_TRY(sc.alloc((void **)&srow, sizeof(int32_t) * (M + 1)));
+        HIP_TRY(sc.alloc((void **)&trow, sizeof(int32_t) * (M + 1)));
+        HIP_TRY(sc.alloc((void **)&item_slot, sizeof(int32_t) * (M + 1)));
+        if (P > 0) {
+            hipLaunchKernelGGL(split_fill_kernel, dim3(blocks_for(P)), dim3(kThreads), 0, 0, P, prow, first,
+                               slotbase, (int32_t)sg, srow, trow, item_slot);
+            HIP_TRY(hipGetLastError());
+        } else {
+            HIP_TRY(hipMemset(srow, 0, sizeof(int32_t)));
+        }
+        int32_t *split = nullptr, *split_slot = nullptr;
         HIP_TRY(sc.alloc((void **)&split, sizeof(int32_t) * (n_split + 1)));
-        HIP_TRY(sc.alloc((void **)&split_first, sizeof(int32_t) * (n_split + 1)));
         HIP_TRY(sc.alloc((void **)&split_slot, sizeof(int32_t) * (n_split + 1)));
-        hipLaunchKernelGGL(split_tables_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, items, first,
-                           qpos, slotbase, split, split_first, split_slot);
+        hipLaunchKernelGGL(split_tables_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, items, qpos,
+                           slotbase, split, split_slot);
         HIP_TRY(hipGetLastError());
         out->n_split = n_split;
         out->n_split_items = n_split_items;
         out->max_item_len = sg < nnz_v ? sg : nnz_v;
         out->trow = trow;
         out->split = split;
-        out->split_first = split_first;
+        out->item_slot = item_slot;
         out->split_slot = split_slot;
         sc.release(trow);
         sc.release(split);
-        sc.release(split_first);
+        sc.release(item_slot);
         sc.release(split_slot);
         final_rowptr = srow;
     }

@@ -180,9 +180,8 @@ int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             int64_t items = std::max<int64_t>(1, ceildiv(l, sg));
             first[p + 1] = first[p] + items;
             if (items > 1) {
-                if (first[p] >= (int64_t(1) << 31) - 1) return PCSR_E_TOO_LARGE;
+                if (slots + items >= (int64_t(1) << 31) - 1) return PCSR_E_TOO_LARGE;
                 h.split_panels.push_back((int32_t)p);
-                h.split_first.push_back((int32_t)first[p]);
                 h.split_slot.push_back((int32_t)slots);
                 slots += items;
             }
@@ -193,6 +192,7 @@ int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         h.M = M;
         h.rowptr.resize(M + 1);
         h.trow.resize(M);
+        h.item_slot.assign(M, -1);
         parallel_for(P, 1 << 14, [&](int64_t lo, int64_t hi) {
             for (int64_t p = lo; p < hi; ++p) {
                 int64_t start = prow[p];
@@ -203,6 +203,11 @@ int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
                 }
             }
         });
+        for (size_t q = 0; q < h.split_panels.size(); ++q) {
+            const int64_t p = h.split_panels[q];
+            for (int64_t it = first[p], s = h.split_slot[q]; it < first[p + 1]; ++it, ++s)
+                h.item_slot[it] = (int32_t)s;
+        }
         h.rowptr[M] = (int32_t)h.nnz_v;
         h.max_item_len = std::min<int64_t>(sg, h.nnz_v);
         balance_xcd_ranges(&h);
@@ -233,6 +238,52 @@ void balance_xcd_ranges(HostPcsr *hp)
         h.xcd_bounds[x] = (int32_t)lo;
     }
     h.xcd_bounds[8] = (int32_t)M;
+}
+
+int schedule_by_column(HostPcsr *hp)
+{
+    HostPcsr &h = *hp;
+    constexpr int64_t kItemCost = 8; // as in balance_xcd_ranges
+    try {
+        const int64_t M = h.M;
+        std::vector<int32_t> longs, shorts;
+        for (int64_t it = 0; it < M; ++it) (h.item_slot[it] >= 0 ? longs : shorts).push_back((int32_t)it);
+        // items of split panels are never empty, so their first column exists
+        std::stable_sort(longs.begin(), longs.end(), [&](int32_t a, int32_t b) {
+            return h.colidx[h.rowptr[a]] < h.colidx[h.rowptr[b]];
+        });
+        // 8 contiguous slices of equal work (vectors + a per-item cost) of a list
+        auto slices = [&](const std::vector<int32_t> &v, int64_t (&b)[9]) {
+            std::vector<int64_t> cum(v.size() + 1, 0);
+            for (size_t i = 0; i < v.size(); ++i)
+                cum[i + 1] = cum[i] + (h.rowptr[v[i] + 1] - h.rowptr[v[i]]) + kItemCost;
+            b[0] = 0;
+            for (int x = 1; x < 8; ++x)
+                b[x] = std::lower_bound(cum.begin(), cum.end(), cum.back() * x / 8) - cum.begin();
+            b[8] = (int64_t)v.size();
+        };
+        int64_t lb[9], sb[9];
+        slices(longs, lb);
+        slices(shorts, sb);
+        h.sched.clear();
+        h.sched.reserve(4 * M);
+        auto emit = [&](int32_t it) {
+            h.sched.push_back(h.rowptr[it]);
+            h.sched.push_back(h.rowptr[it + 1] - h.rowptr[it]);
+            h.sched.push_back(h.trow[it]);
+            h.sched.push_back(h.item_slot[it]);
+        };
+        h.xcd_bounds[0] = 0;
+        for (int x = 0; x < 8; ++x) {
+            // the column-ordered part first: its B rows are shared between the waves of the XCD
+            for (int64_t i = lb[x]; i < lb[x + 1]; ++i) emit(longs[i]);
+            for (int64_t i = sb[x]; i < sb[x + 1]; ++i) emit(shorts[i]);
+            h.xcd_bounds[x + 1] = (int32_t)(h.sched.size() / 4);
+        }
+        return PCSR_OK;
+    } catch (const std::bad_alloc &) {
+        return PCSR_E_OOM;
+    }
 }
 
 int choose_windows(HostPcsr *hp, int32_t win_cols)

@@ -19,10 +19,15 @@ struct HostPcsr {
     // Not part of the format: panels that own more than one work item.  Their C rows
     // are cleared before the kernel accumulates into them.
     std::vector<int32_t> split_panels;
-    // For the q-th such panel: its first work item, and the first of the consecutive
-    // workspace slots its items write their partial rows to (split_slot has one more
-    // entry: the total number of items that belong to split panels).
-    std::vector<int32_t> split_first, split_slot;
+    // For the q-th such panel: the first of the consecutive workspace slots its items
+    // write their partial rows to (one more entry at the end: the total number of items
+    // that belong to split panels); and per work item its slot, -1 for an item that is
+    // the only one of its panel.
+    std::vector<int32_t> split_slot, item_slot;
+    // Column-ordered schedule (empty = items run in index order): four entries per launch
+    // position - first vector, vector count, panel, workspace slot or -1 - of the item
+    // that runs there.  With it, xcd_bounds are positions.
+    std::vector<int32_t> sched;
     int64_t max_item_len = 0;
     // Not part of the format: item boundaries that cut the item sequence into 8 contiguous
     // ranges of equal work (vectors plus a per-item overhead), one per XCD.
@@ -43,6 +48,11 @@ int validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *row
 int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
                const int32_t *colidx, const float *vals, int32_t V, int32_t S, int32_t SG,
                int32_t omega, HostPcsr *out);
+
+// Column-ordered schedule for a balanced handle (needs rowptr / colidx / item_slot on the
+// host): the items of split panels in ascending order of their first column, the other
+// items in index order, both dealt to the 8 XCDs in contiguous equal-work slices.
+int schedule_by_column(HostPcsr *h);
 
 // Picks, per block of win_cols/2 consecutive items, the window of win_cols consecutive
 // columns holding most of the block's vectors (needs h->rowptr / h->colidx on the host).

@@ -23,10 +23,12 @@ struct SpmmArgs {
     // several items stores its partial rows in `ws` (slot-major: (slot*V + v)*K + k) and
     // reduce_split adds them in item order.  ws == nullptr selects the atomic write-back.
     float *ws;
-    const int32_t *split_panels; // n_split, ascending: panels that own more than one item
-    const int32_t *split_first;  // n_split: first item of each such panel
-    const int32_t *split_slot;   // n_split + 1: first workspace slot of each such panel
-    int32_t n_split;
+    const int32_t *item_slot; // M (S only): workspace slot of an item of a split panel, -1 for
+                              // an item that is the only one of its panel
+    // Column-ordered schedule (S only, may be null): for launch position i the record
+    // {first vector, vector count, panel (TRow), workspace slot or -1} of the work item
+    // that runs there.  xb then bounds positions, not items.
+    const int4 *sched;
     // column-window blocking (window kernel only)
     const int32_t *win_start; // per item block: first column of the staged window or -1
     int32_t win_cols;         // rows of B staged in LDS

@@ -153,7 +153,33 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
     }
     const int lg = lane & (LPR - 1);
     if (item_l >= limit) return;
-    const int item = (int)item_l;
+
+    // Everything the item needs to know about itself, fetched in one round trip: its
+    // vector range, the panel it writes to (TRow) and its workspace slot (-1: the only
+    // item of its panel).  A column-ordered schedule keeps these as one 16-byte record
+    // per launch position.
+    int head, tail, panel = (int)item_l, slot = -1;
+    if constexpr (S) {
+        if (a.sched) {
+            const int4 rec = a.sched[item_l];
+            head = rec.x;
+            tail = rec.x + rec.y;
+            panel = rec.z;
+            slot = rec.w;
+        } else {
+            head = a.rowptr[item_l];
+            tail = a.rowptr[item_l + 1];
+            panel = a.trow[item_l];
+            slot = a.item_slot[item_l];
+        }
+    } else {
+        head = a.rowptr[item_l];
+        tail = a.rowptr[item_l + 1];
+    }
+    if constexpr (LPR == 64) {
+        head = __builtin_amdgcn_readfirstlane(head);
+        tail = __builtin_amdgcn_readfirstlane(tail);
+    }
 
     const int kbase = blockIdx.y * (LPR * VEC * REP);
     int kc[REP];
@@ -162,13 +188,6 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
     for (int r = 0; r < REP; ++r) {
         kc[r] = kbase + (r * LPR + lg) * VEC;
         kv[r] = kc[r] < a.K;
-    }
-
-    int head = a.rowptr[item];
-    int tail = a.rowptr[item + 1];
-    if constexpr (LPR == 64) {
-        head = __builtin_amdgcn_readfirstlane(head);
-        tail = __builtin_amdgcn_readfirstlane(tail);
     }
 
     float acc[V][REP][VEC];
@@ -182,10 +201,10 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
     const float *__restrict__ B = a.B;
     const long K = a.K;
 
-    for (int base = head; base < tail; base += LPR) {
+    // one lane's entry of the chunk that starts at `base` (zeros past the end of the range)
+    auto load_entry = [&](int base, int &c, float (&av)[V]) {
         const int idx = base + lg;
-        int c = 0;
-        float av[V];
+        c = 0;
 #pragma unroll
         for (int v = 0; v < V; ++v) av[v] = 0.0f;
         if (idx < tail) {
@@ -199,6 +218,19 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
                 av[1] = t[1];
             }
         }
+    };
+
+    // The next chunk's colIdx/val are requested before the current chunk's gathers, so
+    // that a chunk costs one memory round trip, not two.
+    int c_next;
+    float av_next[V];
+    load_entry(head, c_next, av_next);
+    for (int base = head; base < tail; base += LPR) {
+        const int c = c_next;
+        float av[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) av[v] = av_next[v];
+        load_entry(base + LPR, c_next, av_next);
         const int cnt = min(LPR, tail - base);
 
         float part[V][REP][VEC];
@@ -258,29 +290,10 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
     // of its panel.  An item of a panel that was split (TRow names the panel) either
     // leaves its partial rows in the workspace slot that belongs to it, for the second
     // pass to add in item order, or, without a workspace, accumulates with atomics.
-    int panel = item;
-    bool sole = true;
-    if constexpr (S) {
-        panel = a.trow[item];
-        const bool same_prev = item > 0 && a.trow[item - 1] == panel;
-        const bool same_next = item + 1 < a.M && a.trow[item + 1] == panel;
-        sole = !(same_prev || same_next);
-    }
+    const bool sole = slot < 0;
     float *wrow = nullptr;
     if constexpr (S) {
-        if (!sole && a.ws) {
-            // position of the panel in the ascending list of split panels
-            int lo = 0, hi = a.n_split - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if (a.split_panels[mid] < panel)
-                    lo = mid + 1;
-                else
-                    hi = mid;
-            }
-            const long slot = (long)a.split_slot[lo] + (item - a.split_first[lo]);
-            wrow = a.ws + slot * V * K;
-        }
+        if (!sole && a.ws) wrow = a.ws + (long)slot * V * K;
     }
 #pragma unroll
     for (int v = 0; v < V; ++v) {

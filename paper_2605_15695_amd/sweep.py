@@ -95,7 +95,9 @@ def main(argv=None) -> int:
     ap.add_argument("--quick", action="store_true", help="widest vector only, waves in {2,4}")
     ap.add_argument("--reps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--formats", default="all", help="all | comma list of V:S:SG, e.g. 1:0:0,1:1:64")
+    ap.add_argument("--formats", default="all",
+                    help="all | comma list of V:S:SG[:col_window[:flags]], e.g. 1:0:0,1:1:64,1:1:64:0:64 "
+                         "(flags: PCSR_FLAG_* bits given to pcsr_build, 64 = column-ordered schedule)")
     ap.add_argument("--no-hipsparse", action="store_true")
     ap.add_argument("--reorder", action="store_true",
                     help="sweep the matrix after the library's locality reordering (pcsr_reorder)")
@@ -139,7 +141,7 @@ def main(argv=None) -> int:
                    (1, 0, 0, 512), (1, 0, 0, 1024)]
     else:
         formats = [tuple(int(x) for x in f.split(":")) for f in args.formats.split(",")]
-    formats = [f if len(f) == 4 else f + (0,) for f in formats]      # (V, S, SG, col_window)
+    formats = [f + (0,) * (5 - len(f)) for f in formats]             # (V, S, SG, col_window, build flags)
 
     d_rowptr = torch.from_numpy(g.rowptr).cuda()
     d_colidx = torch.from_numpy(g.colidx).cuda()
@@ -147,14 +149,14 @@ def main(argv=None) -> int:
 
     handles = {}
     for fmt in formats:
-        V, S, SG, CW = fmt
+        V, S, SG, CW, FL = fmt
         t0 = time.time()
         handles[fmt] = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals,
                                      pc.make_params(V=V, S=S, SG=SG, col_window=CW,
-                                                    flags=pc.PCSR_FLAG_NO_VALIDATE))
+                                                    flags=pc.PCSR_FLAG_NO_VALIDATE | FL))
         hit = pc.pcsr_window_stats(handles[fmt])["hit_fraction"]
-        print(f"[sweep] built V={V} S={S} SG={SG} CW={CW} (window hit {hit:.3f}) in {time.time()-t0:.2f}s",
-              flush=True)
+        print(f"[sweep] built V={V} S={S} SG={SG} CW={CW} flags={FL} (window hit {hit:.3f}) in "
+              f"{time.time()-t0:.2f}s", flush=True)
 
     for K in Ks:
         B = synth.dense_operand(g.n_cols, K, spec["B"], 2)
@@ -168,7 +170,7 @@ def main(argv=None) -> int:
                 "bytes_min": bytes_min}
         best = (float("inf"), None)
         for fmt in formats:
-            V, S, SG, CW = fmt
+            V, S, SG, CW, FL = fmt
             h = handles[fmt]
             waves_list = (2, 4) if args.quick else (1, 2, 4, 8)
             ipg_list = (1, 2, 4) if not S else (1,)
@@ -201,14 +203,15 @@ def main(argv=None) -> int:
                     dev = 0.0
                 else:
                     dev = float((Cd - Cref).abs().max().item()) / scale
-                rec = dict(base, kind="pcsr", V=V, S=S, SG=SG, col_window=CW, lanes_per_row=lpr, vec=vec, rep=rep,
+                rec = dict(base, kind="pcsr", V=V, S=S, SG=SG, col_window=CW, build_flags=FL, lanes_per_row=lpr, vec=vec, rep=rep,
                            waves_per_wg=waves, items_per_group=ipg, xcd_remap=remap, grid_x=q["grid_x"], grid_y=q["grid_y"],
                            ms_median=med, ms_min=mn, gflops=flops / med / 1e6,
                            roofline_frac=bytes_min / (med * 1e-3) / 1e9 / HBM_PEAK_GBS, max_rel_dev=dev)
                 emit(rec)
                 if med < best[0]:
                     best = (med, rec)
-            print(f"[sweep] K={K} V={V} S={S} SG={SG} CW={CW} done; best so far {best[0]:.4f} ms", flush=True)
+            print(f"[sweep] K={K} V={V} S={S} SG={SG} CW={CW} flags={FL} done; best so far {best[0]:.4f} ms",
+                  flush=True)
 
         hs_best = (float("inf"), None)
         if not args.no_hipsparse:
@@ -249,7 +252,7 @@ def main(argv=None) -> int:
         best_again = None
         if best[1]:
             b = best[1]
-            hb = handles[(b["V"], b["S"], b["SG"], b["col_window"])]
+            hb = handles[(b["V"], b["S"], b["SG"], b["col_window"], b.get("build_flags", 0))]
             pc.pcsr_set_kernel_params(hb, b["lanes_per_row"], b["vec"], b["rep"], b["waves_per_wg"],
                                       b["items_per_group"], 0 if b["xcd_remap"] else pc.PCSR_FLAG_NO_XCD_REMAP)
             best_again, _ = time_launches(lambda: pc.pcsr_spmm(hb, Bd, Cd, K, stream), stream, torch,
@@ -283,7 +286,7 @@ def main(argv=None) -> int:
         emit(summary)
         b = best[1]
         print(f"[sweep] K={K} BEST {b['ms_median']:.4f} ms {b['gflops']:.0f} GFLOP/s roofline {b['roofline_frac']:.3f} "
-              f"V={b['V']} S={b['S']} SG={b['SG']} CW={b['col_window']} lpr={b['lanes_per_row']} vec={b['vec']} rep={b['rep']} "
+              f"V={b['V']} S={b['S']} SG={b['SG']} CW={b['col_window']} flags={b.get('build_flags', 0)} lpr={b['lanes_per_row']} vec={b['vec']} rep={b['rep']} "
               f"waves={b['waves_per_wg']} ipg={b['items_per_group']} remap={b['xcd_remap']} | hipsparse best "
               f"{hs_best[0]:.4f} ms ({hs_best[1]['alg'] if hs_best[1] else '-'})", flush=True)
         del Bd, Cd, Cref

@@ -422,14 +422,16 @@ def test_largest_workload_where_offsets_need_64_bits(K):
 @pytest.mark.parametrize("V", [1, 2])
 def test_balanced_write_back_is_deterministic_and_needs_no_clean_output(name, V):
     """S = 1 without atomics: two runs over outputs prefilled with different garbage give
-    identical bits; the handle built by GPU kernels gives the same bits as the host-built one;
-    the atomic write-back stays within tolerance of the oracle."""
+    identical bits; the handle built by GPU kernels and the one with the column-ordered
+    schedule (which only changes when an item runs, not what it adds up) give the same bits
+    as the host-built one; the atomic write-back stays within tolerance of the oracle."""
     g = _graph(name)
     K = 48
     B, ref, bound = _oracle(name, g, K, synth.WORKLOADS[name]["B"])
     Bd = torch.from_numpy(B).cuda()
     outs = []
-    for flags in (0, pc.PCSR_FLAG_GPU_BUILD):
+    for flags in (0, pc.PCSR_FLAG_GPU_BUILD, pc.PCSR_FLAG_COLUMN_ORDER,
+                  pc.PCSR_FLAG_COLUMN_ORDER | pc.PCSR_FLAG_NO_XCD_REMAP):
         h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=1, SG=8, flags=flags))
         e = pc.pcsr_export(h)
         n_items = int(np.sum(np.bincount(e["trow"], minlength=e["P"])[np.bincount(e["trow"], minlength=e["P"]) > 1]))
