@@ -67,10 +67,15 @@ def main() -> int:
     ap.add_argument("--items-per-group", type=int, default=0)
     ap.add_argument("--col-window", type=int, default=-1, help="-1 = library selector")
     ap.add_argument("--gpu-build", action="store_true", help="generate the PCSR arrays with GPU kernels")
-    ap.add_argument("--reorder", action="store_true",
-                    help="apply the library's locality reordering first (A' = P A P^T, B' = P B); the timed "
-                         "SpMM runs on the relabelled problem and its result is checked as C = P^T C'")
+    ap.add_argument("--reorder", nargs="?", const="cluster", default=None, choices=["cluster", "degree"],
+                    help="apply one of the library's relabellings first (A' = P A P^T, B' = P B): 'cluster' = "
+                         "label propagation (pcsr_reorder), 'degree' = descending in-degree "
+                         "(pcsr_reorder_by_degree); the timed SpMM runs on the relabelled problem and its "
+                         "result is checked as C = P^T C'")
     ap.add_argument("--no-xcd-remap", action="store_true")
+    ap.add_argument("--index-order", action="store_true",
+                    help="S = 1: run the work items in index order even where the selector asks for the "
+                         "column-ordered schedule")
     ap.add_argument("--atomic-split", action="store_true",
                     help="S = 1: accumulate split panels with fp32 atomics instead of the two-pass write-back")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -109,7 +114,10 @@ def main() -> int:
     g_orig, B_orig = g, B
     if args.reorder:
         t0 = time.time()
-        perm, n_clusters = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
+        if args.reorder == "degree":
+            perm = pc.pcsr_reorder_by_degree(g.n_rows, g.rowptr, g.colidx)
+        else:
+            perm, n_clusters = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
         rp, ci, va = pc.pcsr_permute_csr(g.n_rows, g.rowptr, g.colidx, g.vals, perm)
         reorder_ms = (time.time() - t0) * 1e3
         g = synth.Graph(g.name + "_reordered", g.n_rows, g.n_cols, rp, ci, va)
@@ -129,7 +137,8 @@ def main() -> int:
         rep=args.rep or sel.rep, waves_per_wg=args.waves or sel.waves_per_wg,
         items_per_group=args.items_per_group or sel.items_per_group,
         col_window=sel.col_window if args.col_window < 0 else args.col_window,
-        flags=(pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
+        flags=(sel.flags if S == sel.S and not args.index_order else 0)
+        | (pc.PCSR_FLAG_NO_XCD_REMAP if args.no_xcd_remap else 0)
         | (pc.PCSR_FLAG_GPU_BUILD if args.gpu_build else 0)
         | (pc.PCSR_FLAG_ATOMIC_SPLIT if args.atomic_split else 0))
     t0 = time.time()
@@ -187,7 +196,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}-{args.size}" + ("+reorder" if args.reorder else ""),
+        "config": {"workload": f"{args.workload}-{args.size}" + (f"+reorder({args.reorder})" if args.reorder else ""),
                    "graph": g.name, "n": g.n_rows,
                    "nnz": g.nnz, "K": K, "V": V, "S": S, "SG": int(params.SG), **launch, "kernel": instance,
                    "workspace_bytes": pc.pcsr_workspace_bytes(h, K)},

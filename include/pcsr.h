@@ -50,7 +50,7 @@ enum {
                                   column, dealt to the 8 XCDs as 8 contiguous column ranges,
                                   so that the wavefronts of one XCD gather the same rows of B
                                   at about the same time; all other items run in index order.
-                                  The PCSR arrays do not change.  Built on the host            */
+                                  The PCSR arrays do not change                                */
     PCSR_FLAG_ATOMIC_SPLIT = 32 /* S = 1 only: panels that were split accumulate into C with
                                   fp32 atomics, as Algorithm 2 prints it, instead of the
                                   default two-pass write-back (see pcsr_spmm)                 */
@@ -214,6 +214,16 @@ int pcsr_export(pcsr_handle_t h, int64_t sizes[6], int32_t *rowptr, int32_t *col
                 int32_t *trow);
 
 /*
+ * Launch schedule of the handle, for inspection.  xcd_bounds (host, int32[9], may be NULL):
+ * XCD x processes launch positions [xcd_bounds[x], xcd_bounds[x+1]).  Without
+ * PCSR_FLAG_COLUMN_ORDER position i is work item i and *n_positions is set to 0.  With it
+ * *n_positions = M and sched (host, int32[4*M], may be NULL) receives for every position the
+ * record {first vector, vector count, panel, workspace slot or -1} of the item that runs
+ * there.  Synchronous.  Errors: INVALID_ARG, HIP.
+ */
+int pcsr_export_schedule(pcsr_handle_t h, int64_t *n_positions, int32_t *sched, int32_t xcd_bounds[9]);
+
+/*
  * Sparse-matrix features of Table 3, in this order (host, fp64[PCSR_N_FEATURES]):
  *   n, n_hat, nnz, delta, d, d_hat, d_max, CV, CV_hat, SR_1, SR_2, rho, b, b_max,
  *   PR_1, PR_2      (SR: Eq. (4) under S with Eq. (3)'s SG; PR: Eq. (2)).
@@ -255,6 +265,17 @@ int pcsr_select(const double *features, int32_t K, pcsr_params_t *out);
  */
 int pcsr_reorder(int64_t n, const int32_t *rowptr, const int32_t *colidx, int32_t max_rounds,
                  int32_t *perm, int64_t *n_clusters);
+
+/*
+ * Second relabelling for the same pre-step (Section 4.4), meant for power-law inputs, which
+ * have hubs rather than communities: nodes are numbered by descending in-degree (how often
+ * their row of B is gathered), ties in original order.  The most-gathered rows of B then
+ * sit at the lowest ids, so in every row of A the hub columns come first, and a
+ * column-ordered schedule (PCSR_FLAG_COLUMN_ORDER) runs the hub-only work items together.
+ *   rowptr int32[n+1], colidx int32[nnz]: host.  perm (host, int32[n]): perm[old] = new.
+ * Errors: INVALID_ARG, BAD_CSR (column >= n), TOO_LARGE, OOM.
+ */
+int pcsr_reorder_by_degree(int64_t n, const int32_t *rowptr, const int32_t *colidx, int32_t *perm);
 
 /*
  * Symmetric relabelling of a square CSR matrix: row perm[i] of the output holds row i of

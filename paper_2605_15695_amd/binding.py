@@ -65,11 +65,13 @@ def _lib():
         lib.pcsr_query_launch.argtypes = [vp, i32, ctypes.POINTER(i32 * 8)]
         lib.pcsr_window_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_double * 3)]
         lib.pcsr_export.argtypes = [vp, ctypes.POINTER(i64 * 6), vp, vp, vp, vp]
+        lib.pcsr_export_schedule.argtypes = [vp, ctypes.POINTER(i64), vp, vp]
         lib.pcsr_features.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32]
         lib.pcsr_features_device.argtypes = [i64, i64, i64, vp, vp, i32, vp, i32]
         lib.pcsr_select.argtypes = [vp, i32, pp]
         lib.pcsr_reorder.argtypes = [i64, vp, vp, i32, vp, ctypes.POINTER(i64)]
         lib.pcsr_permute_csr.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
+        lib.pcsr_reorder_by_degree.argtypes = [i64, vp, vp, vp]
         lib.pcsr_transpose_csr.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp]
         lib.pcsr_mac_job_gap.argtypes = [i32, i32, i32]
         lib.pcsr_mac_job_gap.restype = i32
@@ -79,7 +81,8 @@ def _lib():
         for name in ("pcsr_build", "pcsr_spmm", "pcsr_free", "pcsr_set_kernel_params",
                      "pcsr_query_launch", "pcsr_export", "pcsr_features", "pcsr_select",
                      "pcsr_window_stats", "pcsr_features_device", "pcsr_reorder", "pcsr_permute_csr",
-                     "pcsr_transpose_csr", "pcsr_workspace_bytes", "pcsr_reserve_workspace", "pcsr_spmm_static"):
+                     "pcsr_transpose_csr", "pcsr_workspace_bytes", "pcsr_reserve_workspace", "pcsr_spmm_static",
+                     "pcsr_export_schedule", "pcsr_reorder_by_degree"):
             getattr(lib, name).restype = ctypes.c_int
         _LIB = lib
     return _LIB
@@ -247,6 +250,22 @@ def pcsr_export(h: Handle) -> dict:
     return dict(P=P, M=M, nnz_v=nnz_v, V=V, SG=SG, rowptr=rowptr, colidx=colidx, val=val, trow=trow)
 
 
+def pcsr_export_schedule(h: Handle) -> dict:
+    """xcd_bounds int32[9] and, for a column-ordered handle, sched int32[M, 4] (else None)."""
+    n = ctypes.c_int64(0)
+    xb = np.zeros(9, np.int32)
+    rc = _lib().pcsr_export_schedule(h.raw, ctypes.byref(n), None, xb.ctypes.data)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_export_schedule")
+    sched = None
+    if n.value:
+        sched = np.empty((n.value, 4), np.int32)
+        rc = _lib().pcsr_export_schedule(h.raw, ctypes.byref(n), sched.ctypes.data, xb.ctypes.data)
+        if rc != PCSR_OK:
+            raise PcsrError(rc, "pcsr_export_schedule")
+    return dict(xcd_bounds=xb, sched=sched)
+
+
 def pcsr_features(n_rows, n_cols, rowptr, colidx, omega=0) -> np.ndarray:
     """Table 3 features; device tensors are routed to the GPU implementation."""
     k0, p_r, dev_r = _ptr(rowptr, np.dtype(np.int32))
@@ -288,6 +307,17 @@ def pcsr_reorder(n, rowptr, colidx, max_rounds=0):
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_reorder")
     return perm, int(ncl.value)
+
+
+def pcsr_reorder_by_degree(n, rowptr, colidx):
+    """perm int32[n] with perm[old] = new: nodes by descending in-degree."""
+    k0, p_r, _ = _ptr(rowptr, np.dtype(np.int32))
+    k1, p_c, _ = _ptr(colidx, np.dtype(np.int32))
+    perm = np.empty(n, np.int32)
+    rc = _lib().pcsr_reorder_by_degree(n, p_r, p_c, perm.ctypes.data)
+    if rc != PCSR_OK:
+        raise PcsrError(rc, "pcsr_reorder_by_degree")
+    return perm
 
 
 def pcsr_permute_csr(n, rowptr, colidx, vals, perm):

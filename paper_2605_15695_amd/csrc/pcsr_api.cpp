@@ -114,8 +114,8 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
             const int fit = (128 * 1024 / 4 / h->host.win_cols - 4) / vec;
             if (need > fit) need = fit;
         }
-        // balanced (power-law) handles: two or four items per wavefront, as pcsr_select picks
-        const int cap = h->host.S ? (h->host.nnz >= (int64_t(64) << 20) ? 16 : 32) : 64;
+        // balanced (power-law) handles: four items per wavefront, as pcsr_select picks
+        const int cap = h->host.S ? 16 : 64;
         lpr = 4;
         while (lpr < need && lpr < cap) lpr <<= 1;
     }
@@ -123,7 +123,7 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
     if (!rep) {
         int need = (K + lpr * vec - 1) / (lpr * vec);
         rep = 1;
-        if (h->host.win_cols == 0)
+        if (h->host.win_cols == 0 && !h->host.S)
             while (rep < need && rep < 4) rep <<= 1;
     }
     int waves = h->waves ? h->waves : 4;
@@ -204,7 +204,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     const bool device_csr = (prm.flags & PCSR_FLAG_DEVICE_CSR) != 0;
     const bool column_order = (prm.flags & PCSR_FLAG_COLUMN_ORDER) != 0;
     if (column_order && (!prm.S || prm.col_window)) return PCSR_E_UNSUPPORTED;
-    if ((device_csr || (prm.flags & PCSR_FLAG_GPU_BUILD)) && !prm.col_window && !column_order) {
+    if ((device_csr || (prm.flags & PCSR_FLAG_GPU_BUILD)) && !prm.col_window) {
         if (host_only) return PCSR_E_INVALID_ARG;
         // ---- PCSR generation on the GPU
         int32_t *t_rowptr = nullptr, *t_colidx = nullptr;
@@ -233,7 +233,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         pcsr::DeviceBuild db;
         int herr = 0;
         rc = pcsr::build_device(n_rows, n_cols, nnz, rowptr, colidx, vals, prm.V, prm.S, prm.SG, prm.omega,
-                                !(prm.flags & PCSR_FLAG_NO_VALIDATE), &db, &herr);
+                                !(prm.flags & PCSR_FLAG_NO_VALIDATE), column_order, &db, &herr);
         drop_tmp();
         if (rc != PCSR_OK) {
             if (rc == PCSR_E_HIP) g_last_hip = herr;
@@ -247,6 +247,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             if (db.trow) (void)hipFree(db.trow);
             if (db.split) (void)hipFree(db.split);
             if (db.item_slot) (void)hipFree(db.item_slot);
+            if (db.sched) (void)hipFree(db.sched);
             if (db.split_slot) (void)hipFree(db.split_slot);
             return PCSR_E_OOM;
         }
@@ -267,6 +268,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         h->d_trow = db.trow;
         h->d_split = db.split;
         h->d_item_slot = db.item_slot;
+        h->d_sched = db.sched;
         h->d_split_slot = db.split_slot;
         h->n_split = db.n_split;
         h->n_split_items = db.n_split_items;
@@ -286,9 +288,8 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
     }
 
     try {
-        // The column-window build and the column-ordered schedule run on the host: CSR arrays
-        // handed over in device memory are copied there first (every other device-CSR build
-        // took the GPU branch above).
+        // The column-window build runs on the host: CSR arrays handed over in device memory
+        // are copied there first (every other device-CSR build took the GPU branch above).
         std::vector<int32_t> s_rowptr, s_colidx;
         std::vector<float> s_vals;
         if (device_csr) {
@@ -601,6 +602,22 @@ int pcsr_export(pcsr_handle_t h, int64_t sizes[6], int32_t *rowptr, int32_t *col
     return rc;
 }
 
+int pcsr_export_schedule(pcsr_handle_t h, int64_t *n_positions, int32_t *sched, int32_t xcd_bounds[9])
+{
+    if (!valid(h)) return PCSR_E_INVALID_ARG;
+    const bool has = h->host_only ? !h->host.sched.empty() : h->d_sched != nullptr;
+    if (n_positions) *n_positions = has ? h->host.M : 0;
+    if (xcd_bounds)
+        for (int x = 0; x < 9; ++x) xcd_bounds[x] = h->host.xcd_bounds[x];
+    if (!sched || !has || h->host.M == 0) return PCSR_OK;
+    const size_t bytes = sizeof(int32_t) * 4 * (size_t)h->host.M;
+    if (h->host_only) {
+        std::memcpy(sched, h->host.sched.data(), bytes);
+        return PCSR_OK;
+    }
+    return hip_ok(hipMemcpy(sched, h->d_sched, bytes, hipMemcpyDeviceToHost)) ? PCSR_OK : PCSR_E_HIP;
+}
+
 int pcsr_features(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
                   const int32_t *colidx, int32_t omega, double *out, int32_t n_out)
 {
@@ -633,33 +650,35 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     if (K <= 0) return PCSR_E_UNSUPPORTED;
     pcsr_params_t p;
     std::memset(&p, 0, sizeof(p));
-    const double n = f[0], nnz = f[2], d_hat = f[5], d_max = f[6], cv = f[7], rho = f[11];
-    const double bw = f[12], pr2 = f[15];
+    const double d_hat = f[5], d_max = f[6], cv = f[7], pr2 = f[15];
 
     // Balancing (Section 3.2) pays when a few rows dwarf the average one.  On MI355X the
-    // recorded sweeps prefer items far longer than Eq. (3)'s value for such inputs: 256
-    // vectors, and 1024 once the matrix is so large that even then the items outnumber
-    // the wave slots of the chip many times over.
+    // recorded sweeps then prefer short items (32 vectors) run in column order: the items of
+    // the long rows, sorted by first column, make the wavefronts of an XCD gather the same B
+    // rows at about the same time (R-MAT scale 22: 1.6-2x over the best index-order tuple at
+    // every width from 16 to 512; neutral on small or uniform inputs).
     p.S = (cv > 1.5 && d_max > 256.0) ? 1 : 0;
-    p.SG = p.S ? (nnz >= 64.0 * 1048576.0 ? 1024 : 256) : 0;
+    p.SG = p.S ? 32 : 0;
     p.omega = 64;
+    if (p.S) p.flags |= PCSR_FLAG_COLUMN_ORDER;
     // Vector size 2 (Section 3.1) when adjacent rows share columns, and for short rows, where
     // pairing rows doubles the gathers a lane group keeps in flight.  The paper's A6000 data
     // puts the break-even near 30 % padding; on MI355X clique-like inputs win at 11 %
     // padding (1.23x at K=128) and lose at 27 %, because adjacent rows of one wavefront
-    // already share their B lines in L1.
+    // already share their B lines in L1.  Balanced inputs: V = 2 ties or loses in the sweeps.
     p.V = (!p.S && (d_hat < 6.0 || (d_hat < 12.0 && pr2 < 0.45) || pr2 < 0.20)) ? 2 : 1;
 
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.
     const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
-    // Balanced power-law inputs do best with several items per wavefront whatever K is
-    // (two below 64M nonzeros, four above): repeats, then grid.y slices, cover the row.
-    const int lpr_cap = p.S ? (nnz >= 64.0 * 1048576.0 ? 16 : 32) : 64;
+    // Balanced power-law inputs do best with four items per wavefront whatever K is and
+    // no repeats: 64-column slices (grid.y) cover wider rows, which also halves the bytes
+    // a cached B row occupies.
+    const int lpr_cap = p.S ? 16 : 64;
     int lpr = 4;
     while (lpr * vec < K && lpr < lpr_cap) lpr <<= 1;
     int rep = 1;
-    while (lpr * vec * rep < K && rep < 4) rep <<= 1;
+    while (!p.S && lpr * vec * rep < K && rep < 4) rep <<= 1;
     if (!p.S && p.V == 1 && d_hat < 8.0 && lpr >= 32 && rep == 1) {
         lpr >>= 1; // short rows: more rows per wavefront, two loads per lane
         rep = 2;
@@ -672,9 +691,6 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     p.waves_per_wg = p.S ? 4 : (d_hat >= 16.0 ? 8 : 2);
     p.items_per_group = 1;
     p.col_window = 0;
-    (void)n;
-    (void)rho;
-    (void)bw;
     *out = p;
     return PCSR_OK;
 }

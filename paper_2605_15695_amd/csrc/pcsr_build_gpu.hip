@@ -166,6 +166,84 @@ __global__ void split_tables_kernel(int64_t P, const int32_t *items, const int32
     }
 }
 
+// ---- column-ordered schedule (same result as the host builder's schedule_by_column)
+
+// flag[it] = 1 for an item of a split panel (one extra trailing 0 so the scan yields the total)
+__global__ void sched_flag_kernel(int64_t M, const int32_t *item_slot, int32_t *flag)
+{
+    const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (it > M) return;
+    flag[it] = (it < M && item_slot[it] >= 0) ? 1 : 0;
+}
+
+// long items keyed by their first column (in slot order = item order); the others listed in
+// item order.  lrank: exclusive scan of flag.
+__global__ void sched_lists_kernel(int64_t M, const int32_t *rowptr, const int32_t *colidx,
+                                   const int32_t *item_slot, const int32_t *lrank, int32_t *long_key,
+                                   int32_t *long_item, int32_t *short_item)
+{
+    const int64_t it = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (it >= M) return;
+    const int slot = item_slot[it];
+    if (slot >= 0) {
+        long_key[slot] = colidx[rowptr[it]]; // items of split panels are never empty
+        long_item[slot] = (int32_t)it;
+    } else {
+        short_item[it - lrank[it]] = (int32_t)it;
+    }
+}
+
+// w[i] = vectors of list[i] + 8 (the per-item cost), w[n] = 0
+__global__ void sched_weights_kernel(int64_t n, const int32_t *list, const int32_t *rowptr, long long *w)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > n) return;
+    w[i] = i < n ? (long long)(rowptr[list[i] + 1] - rowptr[list[i]]) + 8 : 0;
+}
+
+// 8 contiguous equal-work slices of both lists; cum*: exclusive scans of the weights (n + 1
+// entries, the last one the total).  out: lb[9], sb[9], xb[9].
+__global__ void sched_bounds_kernel(long nl, const long long *cum_l, long ns, const long long *cum_s,
+                                    int32_t *out)
+{
+    const int x = threadIdx.x;
+    if (x > 8) return;
+    auto lower = [](const long long *cum, long n, long long target) {
+        long lo = 0, hi = n + 1; // first index in [0, n] with cum[index] >= target
+        while (lo < hi) {
+            const long mid = (lo + hi) / 2;
+            if (cum[mid] >= target)
+                hi = mid;
+            else
+                lo = mid + 1;
+        }
+        return lo > n ? n : lo;
+    };
+    const long l = x == 0 ? 0 : (x == 8 ? nl : lower(cum_l, nl, cum_l[nl] * x / 8));
+    const long sh = x == 0 ? 0 : (x == 8 ? ns : lower(cum_s, ns, cum_s[ns] * x / 8));
+    out[x] = (int32_t)l;
+    out[9 + x] = (int32_t)sh;
+    out[18 + x] = (int32_t)(l + sh);
+}
+
+// one record per launch position: XCD x runs its slice of the column-ordered list, then
+// its slice of the others
+__global__ void sched_emit_kernel(int64_t n, const int32_t *list, int is_short, const int32_t *bounds,
+                                  const int32_t *rowptr, const int32_t *trow, const int32_t *item_slot,
+                                  int4 *sched)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t *lb = bounds, *sb = bounds + 9;
+    const int32_t *mine = is_short ? sb : lb;
+    int x = 0;
+    while (x < 7 && i >= mine[x + 1]) ++x;
+    const int64_t pos = is_short ? (int64_t)lb[x + 1] + i : (int64_t)sb[x] + i;
+    const int it = list[i];
+    const int start = rowptr[it];
+    sched[pos] = make_int4(start, rowptr[it + 1] - start, trow[it], item_slot[it]);
+}
+
 // 8 contiguous item ranges of equal work (vectors + 8 per item); same rule as the host builder
 __global__ void xcd_bounds_kernel(int32_t M, const int32_t *rowptr, int32_t *xb)
 {
@@ -346,11 +424,95 @@ hipError_t exclusive_scan(const int32_t *in, int32_t *out, int64_t n, Scratch &s
     return e;
 }
 
+hipError_t exclusive_scan64(const long long *in, long long *out, int64_t n, Scratch &sc)
+{
+    size_t bytes = 0;
+    hipError_t e = hipcub::DeviceScan::ExclusiveSum(nullptr, bytes, in, out, (int)n);
+    if (e != hipSuccess) return e;
+    void *tmp = nullptr;
+    e = sc.alloc(&tmp, bytes);
+    if (e != hipSuccess) return e;
+    return hipcub::DeviceScan::ExclusiveSum(tmp, bytes, in, out, (int)n);
+}
+
+// Column-ordered schedule from the balanced arrays (all device pointers): fills *sched_out
+// (4 int32 per launch position, ownership to the caller) and the position bounds per XCD.
+int schedule_by_column_device(int64_t M, int64_t n_long, const int32_t *rowptr, const int32_t *colidx,
+                              const int32_t *trow, const int32_t *item_slot, int32_t **sched_out,
+                              int32_t xcd_bounds[9], int *hip_err)
+{
+    Scratch sc;
+    const int64_t n_short = M - n_long;
+    int32_t *flag = nullptr, *lrank = nullptr, *long_key = nullptr, *long_item = nullptr, *short_item = nullptr;
+    int32_t *key_sorted = nullptr, *long_sorted = nullptr, *d_bounds = nullptr, *sched = nullptr;
+    long long *w_l = nullptr, *w_s = nullptr, *cum_l = nullptr, *cum_s = nullptr;
+    HIP_TRY(sc.alloc((void **)&flag, sizeof(int32_t) * (M + 1)));
+    HIP_TRY(sc.alloc((void **)&lrank, sizeof(int32_t) * (M + 1)));
+    HIP_TRY(sc.alloc((void **)&long_key, sizeof(int32_t) * (n_long + 1)));
+    HIP_TRY(sc.alloc((void **)&long_item, sizeof(int32_t) * (n_long + 1)));
+    HIP_TRY(sc.alloc((void **)&key_sorted, sizeof(int32_t) * (n_long + 1)));
+    HIP_TRY(sc.alloc((void **)&long_sorted, sizeof(int32_t) * (n_long + 1)));
+    HIP_TRY(sc.alloc((void **)&short_item, sizeof(int32_t) * (n_short + 1)));
+    HIP_TRY(sc.alloc((void **)&w_l, sizeof(long long) * (n_long + 1)));
+    HIP_TRY(sc.alloc((void **)&w_s, sizeof(long long) * (n_short + 1)));
+    HIP_TRY(sc.alloc((void **)&cum_l, sizeof(long long) * (n_long + 1)));
+    HIP_TRY(sc.alloc((void **)&cum_s, sizeof(long long) * (n_short + 1)));
+    HIP_TRY(sc.alloc((void **)&d_bounds, sizeof(int32_t) * 27));
+    HIP_TRY(sc.alloc((void **)&sched, sizeof(int32_t) * 4 * (M + 1)));
+
+    hipLaunchKernelGGL(sched_flag_kernel, dim3(blocks_for(M + 1)), dim3(kThreads), 0, 0, M, item_slot, flag);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(exclusive_scan(flag, lrank, M + 1, sc));
+    if (M > 0) {
+        hipLaunchKernelGGL(sched_lists_kernel, dim3(blocks_for(M)), dim3(kThreads), 0, 0, M, rowptr, colidx,
+                           item_slot, lrank, long_key, long_item, short_item);
+        HIP_TRY(hipGetLastError());
+    }
+    if (n_long > 0) {
+        // stable: equal first columns stay in item order, as on the host
+        size_t bytes = 0;
+        HIP_TRY(hipcub::DeviceRadixSort::SortPairs(nullptr, bytes, long_key, key_sorted, long_item, long_sorted,
+                                                   (int)n_long));
+        void *tmp = nullptr;
+        HIP_TRY(sc.alloc(&tmp, bytes));
+        HIP_TRY(hipcub::DeviceRadixSort::SortPairs(tmp, bytes, long_key, key_sorted, long_item, long_sorted,
+                                                   (int)n_long));
+    }
+    hipLaunchKernelGGL(sched_weights_kernel, dim3(blocks_for(n_long + 1)), dim3(kThreads), 0, 0, n_long,
+                       long_sorted, rowptr, w_l);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(sched_weights_kernel, dim3(blocks_for(n_short + 1)), dim3(kThreads), 0, 0, n_short,
+                       short_item, rowptr, w_s);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(exclusive_scan64(w_l, cum_l, n_long + 1, sc));
+    HIP_TRY(exclusive_scan64(w_s, cum_s, n_short + 1, sc));
+    hipLaunchKernelGGL(sched_bounds_kernel, dim3(1), dim3(64), 0, 0, (long)n_long, cum_l, (long)n_short, cum_s,
+                       d_bounds);
+    HIP_TRY(hipGetLastError());
+    if (n_long > 0) {
+        hipLaunchKernelGGL(sched_emit_kernel, dim3(blocks_for(n_long)), dim3(kThreads), 0, 0, n_long, long_sorted,
+                           0, d_bounds, rowptr, trow, item_slot, reinterpret_cast<int4 *>(sched));
+        HIP_TRY(hipGetLastError());
+    }
+    if (n_short > 0) {
+        hipLaunchKernelGGL(sched_emit_kernel, dim3(blocks_for(n_short)), dim3(kThreads), 0, 0, n_short, short_item,
+                           1, d_bounds, rowptr, trow, item_slot, reinterpret_cast<int4 *>(sched));
+        HIP_TRY(hipGetLastError());
+    }
+    int32_t h_bounds[27];
+    HIP_TRY(hipMemcpy(h_bounds, d_bounds, sizeof(h_bounds), hipMemcpyDeviceToHost));
+    for (int x = 0; x < 9; ++x) xcd_bounds[x] = h_bounds[18 + x];
+    HIP_TRY(hipDeviceSynchronize());
+    *sched_out = sched;
+    sc.release(sched);
+    return PCSR_OK;
+}
+
 } // namespace
 
 int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_rowptr,
                  const int32_t *d_colidx, const float *d_vals, int32_t V, int32_t S, int32_t SG,
-                 int32_t omega, bool validate, DeviceBuild *out, int *hip_err)
+                 int32_t omega, bool validate, bool column_order, DeviceBuild *out, int *hip_err)
 {
     if (V != 1 && V != 2) return PCSR_E_UNSUPPORTED;
     if (omega == 0) omega = 64;
@@ -505,6 +667,20 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipMemcpy(out->xcd_bounds, d_xb, 9 * sizeof(int32_t), hipMemcpyDeviceToHost));
     HIP_TRY(hipDeviceSynchronize());
+    out->sched = nullptr;
+    if (S && column_order) {
+        const int rc = schedule_by_column_device(M, out->n_split_items, final_rowptr, pcol, out->trow,
+                                                 out->item_slot, &out->sched, out->xcd_bounds, hip_err);
+        if (rc != PCSR_OK) {
+            // the arrays already handed to *out go back to the caller's clean-up
+            (void)hipFree(out->trow);
+            (void)hipFree(out->split);
+            (void)hipFree(out->item_slot);
+            (void)hipFree(out->split_slot);
+            out->trow = out->split = out->item_slot = out->split_slot = nullptr;
+            return rc;
+        }
+    }
 
     out->rowptr = final_rowptr;
     out->colidx = pcol;

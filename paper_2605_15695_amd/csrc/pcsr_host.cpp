@@ -246,12 +246,22 @@ int schedule_by_column(HostPcsr *hp)
     constexpr int64_t kItemCost = 8; // as in balance_xcd_ranges
     try {
         const int64_t M = h.M;
+        // (first column, item) packed in one key: ascending column, ties in item order.  Items
+        // of split panels are never empty, so their first column exists.
+        std::vector<uint64_t> keyed;
         std::vector<int32_t> longs, shorts;
-        for (int64_t it = 0; it < M; ++it) (h.item_slot[it] >= 0 ? longs : shorts).push_back((int32_t)it);
-        // items of split panels are never empty, so their first column exists
-        std::stable_sort(longs.begin(), longs.end(), [&](int32_t a, int32_t b) {
-            return h.colidx[h.rowptr[a]] < h.colidx[h.rowptr[b]];
-        });
+        keyed.reserve(h.split_slot.empty() ? 0 : h.split_slot.back());
+        shorts.reserve(M - (int64_t)keyed.capacity());
+        for (int64_t it = 0; it < M; ++it) {
+            if (h.item_slot[it] >= 0)
+                keyed.push_back(((uint64_t)(uint32_t)h.colidx[h.rowptr[it]] << 32) | (uint32_t)it);
+            else
+                shorts.push_back((int32_t)it);
+        }
+        std::sort(keyed.begin(), keyed.end());
+        longs.resize(keyed.size());
+        for (size_t i = 0; i < keyed.size(); ++i) longs[i] = (int32_t)(keyed[i] & 0xffffffffu);
+        std::vector<uint64_t>().swap(keyed);
         // 8 contiguous slices of equal work (vectors + a per-item cost) of a list
         auto slices = [&](const std::vector<int32_t> &v, int64_t (&b)[9]) {
             std::vector<int64_t> cum(v.size() + 1, 0);

@@ -306,7 +306,11 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
                     if (sole) {
                         store_vec<VEC>(crow + kc[r], acc[v][r]);
                     } else if (wrow) {
+#ifdef PCSR_WS_NT_STORE
+                        store_vec<VEC>(crow + kc[r], acc[v][r]);
+#else
                         store_vec_cached<VEC>(crow + kc[r], acc[v][r]);
+#endif
                     } else {
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) atomicAdd(crow + kc[r] + e, acc[v][r][e]);
@@ -637,38 +641,49 @@ __global__ void __launch_bounds__(256) zero_panels_kernel(const int32_t *__restr
     }
 }
 
-// One thread per element (q, v, k) of the rows of split panels.  The partial rows of
-// panel q sit in consecutive workspace slots in item order and are added in that order,
-// whatever the grid looks like, so the balanced result is the same bits on every run.
+// One thread per VEC consecutive elements (q, v, k..k+VEC) of the rows of split panels.  The
+// partial rows of panel q sit in consecutive workspace slots in item order and are added in
+// that order, whatever the grid looks like, so the balanced result is the same bits on
+// every run.
+template <int VEC>
 __global__ void __launch_bounds__(256) reduce_split_kernel(const int32_t *__restrict__ split_panels,
                                                            const int32_t *__restrict__ split_slot,
                                                            long n_split, int V, const float *__restrict__ ws,
                                                            float *C, int n_rows, int K)
 {
-    const long total = n_split * V * (long)K;
-    for (long t = (long)blockIdx.x * blockDim.x + threadIdx.x; t < total;
-         t += (long)gridDim.x * blockDim.x) {
-        const long r = t / K;
-        const int k = (int)(t - r * K);
-        const long q = r / V;
-        const int v = (int)(r - q * V);
-        const long row = (long)split_panels[q] * V + v;
-        if (row >= n_rows) continue;
-        const long s0 = split_slot[q], s1 = split_slot[q + 1];
-        const long stride = (long)V * K;
-        const float *w = ws + (s0 * V + v) * (long)K + k;
-        float sum = 0.0f;
-        long j = s0;
-        for (; j + 8 <= s1; j += 8, w += 8 * stride) { // eight loads in flight, adds in item order
-            float t[8];
+    const int kv = K / VEC; // vectors per row
+    const long total = n_split * V * (long)kv;
+    const long t = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    const long r = t / kv;
+    const int k = (int)(t - r * kv) * VEC;
+    const long q = r / V;
+    const int v = (int)(r - q * V);
+    const long row = (long)split_panels[q] * V + v;
+    if (row >= n_rows) return;
+    const long s0 = split_slot[q], s1 = split_slot[q + 1];
+    const long stride = (long)V * K;
+    const float *w = ws + (s0 * V + v) * (long)K + k;
+    float sum[VEC];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = w[u * stride];
+    for (int e = 0; e < VEC; ++e) sum[e] = 0.0f;
+    long j = s0;
+    for (; j + 4 <= s1; j += 4, w += 4 * stride) { // four loads in flight, adds in item order
+        float t4[4][VEC];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) sum += t[u];
-        }
-        for (; j < s1; ++j, w += stride) sum += w[0];
-        __builtin_nontemporal_store(sum, C + row * K + k);
+        for (int u = 0; u < 4; ++u) load_vec<VEC>(w + u * stride, t4[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sum[e] += t4[u][e];
     }
+    for (; j < s1; ++j, w += stride) {
+        float t1[VEC];
+        load_vec<VEC>(w, t1);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum[e] += t1[e];
+    }
+    store_vec<VEC>(C + row * K + k, sum);
 }
 
 using KernelFn = void (*)(SpmmArgs);
@@ -862,11 +877,19 @@ hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split
                                hipStream_t stream)
 {
     if (n_split <= 0) return hipSuccess;
-    const long total = n_split * V * (long)K;
-    long blocks = (total + 255) / 256;
-    if (blocks > 256 * 64) blocks = 256 * 64;
-    hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, split_panels,
-                       split_slot, (long)n_split, V, ws, C, n_rows, K);
+    // 16-byte accesses need rows that start on 16-byte boundaries (the workspace always does)
+    const bool aligned = K % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(ws) % 16 == 0;
+    const int vec = aligned ? 4 : 1;
+    const long total = n_split * V * (long)(K / vec);
+    const long blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    if (vec == 4)
+        hipLaunchKernelGGL(reduce_split_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, split_panels,
+                           split_slot, (long)n_split, V, ws, C, n_rows, K);
+    else
+        hipLaunchKernelGGL(reduce_split_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, split_panels,
+                           split_slot, (long)n_split, V, ws, C, n_rows, K);
     return hipGetLastError();
 }
 

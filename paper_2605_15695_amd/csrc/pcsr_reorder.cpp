@@ -123,6 +123,29 @@ int pcsr_reorder(int64_t n, const int32_t *rowptr, const int32_t *colidx, int32_
     }
 }
 
+int pcsr_reorder_by_degree(int64_t n, const int32_t *rowptr, const int32_t *colidx, int32_t *perm)
+{
+    if (n < 0 || !rowptr || !perm) return PCSR_E_INVALID_ARG;
+    if (n >= (int64_t(1) << 31) - 1) return PCSR_E_TOO_LARGE;
+    const int64_t nnz = rowptr[n];
+    if (nnz < 0 || (nnz > 0 && !colidx)) return PCSR_E_INVALID_ARG;
+    try {
+        // how often each node is gathered: its in-degree
+        std::vector<int64_t> refs(n, 0);
+        for (int64_t p = 0; p < nnz; ++p) {
+            if (colidx[p] < 0 || colidx[p] >= n) return PCSR_E_BAD_CSR;
+            ++refs[colidx[p]];
+        }
+        std::vector<int32_t> order(n);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return refs[a] > refs[b]; });
+        for (int64_t k = 0; k < n; ++k) perm[order[k]] = (int32_t)k;
+        return PCSR_OK;
+    } catch (const std::bad_alloc &) {
+        return PCSR_E_OOM;
+    }
+}
+
 int pcsr_permute_csr(int64_t n, const int32_t *rowptr, const int32_t *colidx, const float *vals,
                      const int32_t *perm, int32_t *out_rowptr, int32_t *out_colidx, float *out_vals)
 {

@@ -99,8 +99,9 @@ def main(argv=None) -> int:
                     help="all | comma list of V:S:SG[:col_window[:flags]], e.g. 1:0:0,1:1:64,1:1:64:0:64 "
                          "(flags: PCSR_FLAG_* bits given to pcsr_build, 64 = column-ordered schedule)")
     ap.add_argument("--no-hipsparse", action="store_true")
-    ap.add_argument("--reorder", action="store_true",
-                    help="sweep the matrix after the library's locality reordering (pcsr_reorder)")
+    ap.add_argument("--reorder", nargs="?", const="cluster", default=None, choices=["cluster", "degree"],
+                    help="sweep the matrix after one of the library's relabellings: 'cluster' (pcsr_reorder) "
+                         "or 'degree' (pcsr_reorder_by_degree)")
     ap.add_argument("--shapes", default=None,
                     help="explicit launch shapes instead of the enumeration: comma list of "
                          "lanes:vec:rep:waves:items_per_group")
@@ -127,7 +128,10 @@ def main(argv=None) -> int:
           flush=True)
     if args.reorder:
         t0 = time.time()
-        perm, ncl = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
+        if args.reorder == "degree":
+            perm, ncl = pc.pcsr_reorder_by_degree(g.n_rows, g.rowptr, g.colidx), 0
+        else:
+            perm, ncl = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
         rp, ci, va = pc.pcsr_permute_csr(g.n_rows, g.rowptr, g.colidx, g.vals, perm)
         g = synth.Graph(g.name + "_reordered", g.n_rows, g.n_cols, rp, ci, va)
         print(f"[sweep] reordered into {ncl} clusters in {time.time()-t0:.2f}s", flush=True)
@@ -166,7 +170,7 @@ def main(argv=None) -> int:
         Cref = None
         flops = 2.0 * g.nnz * K
         bytes_min = algorithmic_bytes(g, K)
-        base = {"workload": args.workload + ("+reorder" if args.reorder else ""), "size": args.size, "K": K, "nnz": g.nnz, "n": g.n_rows,
+        base = {"workload": args.workload + (f"+reorder({args.reorder})" if args.reorder else ""), "size": args.size, "K": K, "nnz": g.nnz, "n": g.n_rows,
                 "bytes_min": bytes_min}
         best = (float("inf"), None)
         for fmt in formats:

@@ -12,7 +12,7 @@ import oracle
 import paper_2605_15695_amd as pc
 from oracle import pcsr_format as pf
 import synth
-from tests.helpers import random_csr
+from tests.helpers import column_ordered_schedule, random_csr
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -431,7 +431,8 @@ def test_balanced_write_back_is_deterministic_and_needs_no_clean_output(name, V)
     Bd = torch.from_numpy(B).cuda()
     outs = []
     for flags in (0, pc.PCSR_FLAG_GPU_BUILD, pc.PCSR_FLAG_COLUMN_ORDER,
-                  pc.PCSR_FLAG_COLUMN_ORDER | pc.PCSR_FLAG_NO_XCD_REMAP):
+                  pc.PCSR_FLAG_COLUMN_ORDER | pc.PCSR_FLAG_NO_XCD_REMAP,
+                  pc.PCSR_FLAG_COLUMN_ORDER | pc.PCSR_FLAG_GPU_BUILD):
         h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=1, SG=8, flags=flags))
         e = pc.pcsr_export(h)
         n_items = int(np.sum(np.bincount(e["trow"], minlength=e["P"])[np.bincount(e["trow"], minlength=e["P"]) > 1]))
@@ -451,6 +452,34 @@ def test_balanced_write_back_is_deterministic_and_needs_no_clean_output(name, V)
     _check(outs[0], ref, bound, f"{name} V={V} two-pass write-back")
     for o in outs[1:]:
         assert np.array_equal(outs[0].view(np.uint32), o.view(np.uint32))
+
+
+@pytest.mark.parametrize("name", ["rmat20", "rmat22", "sbm", "poisson"])
+@pytest.mark.parametrize("V,SG", [(1, 4), (2, 16), (1, 0)])
+@pytest.mark.parametrize("device_csr", [False, True])
+def test_column_ordered_schedule_built_on_the_gpu(name, V, SG, device_csr):
+    """The schedule generated by GPU kernels equals the numpy restatement (and so the host
+    builder's), and the handle computes the right product."""
+    g = _graph(name)
+    arrs = [g.rowptr, g.colidx, g.vals]
+    flags = pc.PCSR_FLAG_COLUMN_ORDER
+    if device_csr:
+        arrs = [torch.from_numpy(x).cuda() for x in arrs]
+    else:
+        flags |= pc.PCSR_FLAG_GPU_BUILD
+    h = pc.pcsr_build(g.n_rows, g.n_cols, *arrs, pc.make_params(V=V, S=1, SG=SG, flags=flags))
+    e = pc.pcsr_export(h)
+    got = pc.pcsr_export_schedule(h)
+    sched, xb = column_ordered_schedule(e["rowptr"], e["colidx"], e["trow"], e["P"])
+    assert np.array_equal(got["xcd_bounds"], xb)
+    assert np.array_equal(got["sched"], sched)
+    K = 24
+    B, ref, bound = _oracle(name, g, K, synth.WORKLOADS[name]["B"])
+    Cd = torch.full((g.n_rows, K), float("nan"), dtype=torch.float32, device="cuda")
+    pc.pcsr_spmm(h, torch.from_numpy(B).cuda(), Cd, K)
+    torch.cuda.synchronize()
+    _check(Cd.cpu().numpy(), ref, bound, f"gpu-built column order {name} V={V} SG={SG}")
+    h.close()
 
 
 def test_workspace_grows_with_k_and_can_be_reserved_before_capture():

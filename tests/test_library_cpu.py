@@ -11,7 +11,7 @@ import paper_2605_15695_amd as pc
 from oracle import pcsr_format as pf
 import synth
 from paper_2605_15695_amd import binding
-from tests.helpers import random_csr
+from tests.helpers import column_ordered_schedule, random_csr
 
 ROOT = pathlib.Path(__file__).resolve().parent.parent
 HOST = pc.PCSR_FLAG_HOST_ONLY
@@ -246,3 +246,42 @@ def test_transpose_csr_host():
     with pytest.raises(pc.PcsrError):
         pc.pcsr_transpose_csr(2, 2, np.array([0, 1, 2], np.int32), np.array([0, 7], np.int32),
                               np.ones(2, np.float32))
+
+
+@pytest.mark.parametrize("name", ["rmat20", "rmat22", "sbm", "poisson"])
+@pytest.mark.parametrize("V,SG", [(1, 4), (2, 16), (1, 0)])
+def test_column_ordered_schedule_host(name, V, SG):
+    g = synth.workload(name, "small")
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals,
+                      pc.make_params(V=V, S=1, SG=SG, flags=HOST | pc.PCSR_FLAG_COLUMN_ORDER))
+    e = pc.pcsr_export(h)
+    got = pc.pcsr_export_schedule(h)
+    sched, xb = column_ordered_schedule(e["rowptr"], e["colidx"], e["trow"], e["P"])
+    assert np.array_equal(got["xcd_bounds"], xb)
+    assert np.array_equal(got["sched"], sched)
+    # a permutation of the items: every vector range appears exactly once
+    assert np.array_equal(np.sort(got["sched"][:, 0] * 1), np.sort(e["rowptr"][:-1]))
+    h.close()
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(V=V, S=1, SG=SG, flags=HOST))
+    assert pc.pcsr_export_schedule(h)["sched"] is None
+    h.close()
+    with pytest.raises(pc.PcsrError):                       # needs balancing
+        pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals,
+                      pc.make_params(V=V, S=0, flags=HOST | pc.PCSR_FLAG_COLUMN_ORDER))
+
+
+def test_reorder_by_degree():
+    g = synth.workload("rmat20", "small")
+    perm = pc.pcsr_reorder_by_degree(g.n_rows, g.rowptr, g.colidx)
+    assert np.array_equal(np.sort(perm), np.arange(g.n_rows))
+    indeg = np.bincount(g.colidx, minlength=g.n_cols)
+    # new id = rank by descending in-degree, ties in original order
+    expect = np.empty(g.n_rows, np.int32)
+    expect[np.argsort(-indeg, kind="stable")] = np.arange(g.n_rows)
+    assert np.array_equal(perm, expect)
+    rp, ci, va = pc.pcsr_permute_csr(g.n_rows, g.rowptr, g.colidx, g.vals, perm)
+    indeg2 = np.bincount(ci, minlength=g.n_cols)
+    assert np.all(np.diff(indeg2) <= 0)                      # hubs first
+    with pytest.raises(pc.PcsrError):
+        pc.pcsr_reorder_by_degree(2, np.array([0, 1, 2], np.int32), np.array([0, 5], np.int32))
+    assert pc.pcsr_reorder_by_degree(0, np.zeros(1, np.int32), np.zeros(0, np.int32)).size == 0
