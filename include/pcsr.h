@@ -63,14 +63,16 @@ enum {
  *     S      0/1 workload balancing (Section 3.2): cap every work item at SG vectors.
  *     SG     split granularity; 0 = Eq. (3) with `omega`, > 0 = use as given.
  *     omega  lane count used by Eq. (3); 0 = 64 (wavefront).  32 gives the paper's SG.
- *     col_window  column-window blocking: 0 = off, else 256, 512, 1024 or 2048.  Work
- *            items are grouped into blocks of col_window/2 consecutive items; for each
- *            block the build picks the window of col_window consecutive columns that
- *            holds most of its nonzeros.  The kernel stages that window of B (one
- *            grid.y column slice of it) in LDS and gathers from there; nonzeros outside
- *            the window are gathered from memory as usual.  The PCSR arrays themselves
- *            do not change.  Needs S = 0 and col_window*lanes_per_row*vec*rep*4 bytes
- *            of LDS <= 160 KiB at launch.
+ *     col_window  column-window blocking: 0 = off, else 256, 512, 1024 or 2048.  Consecutive
+ *            work items are cut into blocks of at most col_window items: a block ends
+ *            where the rows stop gathering from the stretch of col_window consecutive
+ *            columns its first rows use (a community of a clustered graph becomes one
+ *            block).  For each block the build picks the window of col_window columns
+ *            that holds most of its nonzeros; the kernel stages that window of B (one
+ *            grid.y column slice of it) in LDS and gathers from there, and nonzeros
+ *            outside the window are gathered from memory as usual.  The PCSR arrays
+ *            themselves do not change.  Needs S = 0 and
+ *            (col_window + 1)*(lanes_per_row*vec*rep + 4)*4 bytes of LDS <= 160 KiB at launch.
  *   Kernel parameters (launch shape only; the paper's F and W):
  *     lanes_per_row  lanes cooperating on one work item: 4, 8, 16, 32 or 64; 0 = auto.
  *     vec            fp32 values per lane per B load: 1, 2 or 4; must divide K; 0 = auto.
@@ -197,8 +199,8 @@ int pcsr_set_kernel_params(pcsr_handle_t h, int32_t lanes_per_row, int32_t vec, 
 int pcsr_query_launch(pcsr_handle_t h, int32_t K, int32_t out[8]);
 
 /*
- * Column-window blocking as built into the handle (host, fp64[3]): col_window, work
- * items per block, fraction of nonzero vectors that fall inside their block's window
+ * Column-window blocking as built into the handle (host, fp64[3]): col_window, average
+ * work items per block, fraction of nonzero vectors that fall inside their block's window
  * (0 when col_window is off).  Errors: INVALID_ARG.
  */
 int pcsr_window_stats(pcsr_handle_t h, double out[3]);

@@ -230,7 +230,7 @@ def pcsr_window_stats(h: Handle) -> dict:
     rc = _lib().pcsr_window_stats(h.raw, ctypes.byref(out))
     if rc != PCSR_OK:
         raise PcsrError(rc, "pcsr_window_stats")
-    return dict(col_window=int(out[0]), items_per_block=int(out[1]), hit_fraction=float(out[2]))
+    return dict(col_window=int(out[0]), items_per_block=float(out[1]), hit_fraction=float(out[2]))
 
 
 def pcsr_export(h: Handle) -> dict:

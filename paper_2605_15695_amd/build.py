@@ -51,5 +51,40 @@ def build(verbose: bool = False) -> pathlib.Path:
     return LIB
 
 
+def resources() -> str:
+    """Registers, scratch and occupancy of every kernel in pcsr_kernels.hip as the compiler
+    reports them (-Rpass-analysis=kernel-resource-usage), as a markdown table."""
+    import re
+
+    OBJ.mkdir(exist_ok=True)
+    cmd = [HIPCC, *COMMON, *DEVICE, "-Rpass-analysis=kernel-resource-usage", "-c", str(CSRC / "pcsr_kernels.hip"),
+           "-o", str(OBJ / "resources.o")]
+    r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(r.stderr)
+    blocks = re.split(r"remark: Function Name: ", r.stderr)[1:]
+    names = subprocess.run(["c++filt"], input="\n".join(b.split()[0] for b in blocks), capture_output=True,
+                           text=True).stdout.strip().split("\n")
+    rows = []
+    for b, name in zip(blocks, names):
+        def field(key):
+            m = re.search(key + r": (\d+)", b)
+            return int(m.group(1)) if m else -1
+        short = name.replace("void pcsr::(anonymous namespace)::", "").replace("pcsr::(anonymous namespace)::", "")
+        short = short.split("(")[0]
+        rows.append((short, field("    VGPRs"), field("TotalSGPRs"), field(r"ScratchSize \[bytes/lane\]"),
+                     field(r"Occupancy \[waves/SIMD\]")))
+    rows.sort()
+    lines = ["| kernel instance | VGPRs | SGPRs | scratch bytes/lane | waves/SIMD the registers allow |",
+             "|---|---|---|---|---|"]
+    lines += [f"| `{n}` | {v} | {sg} | {sc} | {occ} |" for n, v, sg, sc, occ in rows]
+    return "\n".join(lines)
+
+
 if __name__ == "__main__":
-    build(verbose=True)
+    import sys
+
+    if "--resources" in sys.argv:
+        print(resources())
+    else:
+        build(verbose=True)

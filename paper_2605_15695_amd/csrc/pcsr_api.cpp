@@ -54,7 +54,11 @@ struct pcsr_handle_s {
     int32_t *d_item_slot = nullptr;   // per item: workspace slot, -1 for a sole item (S only)
     int32_t *d_sched = nullptr;       // column-ordered schedule: 4 int32 per launch position
     int32_t *d_split_slot = nullptr;  // their first workspace slots (n_split + 1 entries)
-    int32_t *d_win = nullptr;
+    int32_t *d_win = nullptr;     // window start per item block
+    int32_t *d_win_ptr = nullptr; // item range per item block
+    int32_t *d_win_lo = nullptr;  // per item: run of vectors inside the block's window
+    int32_t *d_win_hi = nullptr;
+    int64_t n_win_blocks = 0;
     int64_t n_split = 0;
     int64_t n_split_items = 0; // workspace slots: items that belong to split panels
     float *d_ws = nullptr;     // partial rows of those items, grown on demand
@@ -77,9 +81,13 @@ void release_device(pcsr_handle_t h)
     if (h->d_sched) (void)hipFree(h->d_sched);
     if (h->d_split_slot) (void)hipFree(h->d_split_slot);
     if (h->d_win) (void)hipFree(h->d_win);
+    if (h->d_win_ptr) (void)hipFree(h->d_win_ptr);
+    if (h->d_win_lo) (void)hipFree(h->d_win_lo);
+    if (h->d_win_hi) (void)hipFree(h->d_win_hi);
     if (h->d_ws) (void)hipFree(h->d_ws);
     h->d_rowptr = h->d_colidx = h->d_trow = h->d_split = h->d_win = nullptr;
-    h->d_item_slot = h->d_sched = h->d_split_slot = nullptr;
+    h->d_item_slot = h->d_sched = h->d_split_slot = h->d_win_ptr = nullptr;
+    h->d_win_lo = h->d_win_hi = nullptr;
     h->d_val = h->d_ws = nullptr;
     h->ws_bytes = 0;
 }
@@ -137,15 +145,16 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
     ls->lds_bytes = 0;
     int64_t gx;
     if (h->host.win_cols > 0) {
-        // column-window kernel: one workgroup per block of win_items work items
+        // column-window kernel: one workgroup per item block
         if (h->host.S || ipg > 1) return PCSR_E_UNSUPPORTED;
         if (!pcsr::window_kernel_exists(h->host.V, lpr, vec, rep)) return PCSR_E_UNSUPPORTED;
-        const int64_t lds = (int64_t)h->host.win_cols * (tile + 4) * 4; // rows padded by 4 floats
+        // win_cols rows of B and one row of zeros, each padded by 4 floats
+        const int64_t lds = ((int64_t)h->host.win_cols + 1) * (tile + 4) * 4;
         if (lds > 160 * 1024) return PCSR_E_UNSUPPORTED;
         if (!h->waves) waves = 16;
         ls->window = 1;
         ls->lds_bytes = (int32_t)lds;
-        gx = (h->host.M + h->host.win_items - 1) / h->host.win_items;
+        gx = h->n_win_blocks;
     } else {
         if (waves > 8) return PCSR_E_UNSUPPORTED;
         if (!pcsr::kernel_exists(h->host.V, h->host.S, lpr, vec, rep, ipg)) return PCSR_E_UNSUPPORTED;
@@ -334,6 +343,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
                 return rc;
             }
         }
+        h->n_win_blocks = (int64_t)h->host.win_start.size();
         h->host_only = host_only;
         h->lpr = prm.lanes_per_row;
         h->vec = prm.vec;
@@ -357,6 +367,9 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             if (rc == PCSR_OK && !h->host.sched.empty()) rc = upload(h->host.sched, &h->d_sched);
             if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_slot, &h->d_split_slot);
             if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_start, &h->d_win);
+            if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_ptr, &h->d_win_ptr);
+            if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_lo, &h->d_win_lo);
+            if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_hi, &h->d_win_hi);
             if (rc != PCSR_OK) {
                 release_device(h);
                 delete h;
@@ -372,6 +385,9 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             std::vector<int32_t>().swap(h->host.sched);
             std::vector<int32_t>().swap(h->host.split_slot);
             std::vector<int32_t>().swap(h->host.win_start);
+            std::vector<int32_t>().swap(h->host.win_ptr);
+            std::vector<int32_t>().swap(h->host.win_lo);
+            std::vector<int32_t>().swap(h->host.win_hi);
         }
         *out = h;
         return PCSR_OK;
@@ -443,7 +459,9 @@ static int spmm_enqueue(pcsr_handle_t h, const float *B, float *C, int32_t K, co
     a.sched = reinterpret_cast<const int4 *>(h->d_sched);
     a.win_start = h->d_win;
     a.win_cols = h->host.win_cols;
-    a.win_items = h->host.win_items;
+    a.win_ptr = h->d_win_ptr;
+    a.win_lo = h->d_win_lo;
+    a.win_hi = h->d_win_hi;
     a.n_cols = (int32_t)h->host.n_cols;
     if (!hip_ok(pcsr::launch_spmm(h->host.V, h->host.S, ls, a, s))) return PCSR_E_HIP;
     if (two_pass) {
@@ -569,7 +587,7 @@ int pcsr_window_stats(pcsr_handle_t h, double out[3])
 {
     if (!valid(h) || !out) return PCSR_E_INVALID_ARG;
     out[0] = (double)h->host.win_cols;
-    out[1] = (double)h->host.win_items;
+    out[1] = h->n_win_blocks ? (double)h->host.M / (double)h->n_win_blocks : 0.0;
     out[2] = h->host.win_hit;
     return PCSR_OK;
 }
@@ -653,12 +671,12 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     const double d_hat = f[5], d_max = f[6], cv = f[7], pr2 = f[15];
 
     // Balancing (Section 3.2) pays when a few rows dwarf the average one.  On MI355X the
-    // recorded sweeps then prefer short items (32 vectors) run in column order: the items of
+    // recorded sweeps then prefer short items (64 vectors, 32 from K = 256) run in column order: the items of
     // the long rows, sorted by first column, make the wavefronts of an XCD gather the same B
     // rows at about the same time (R-MAT scale 22: 1.6-2x over the best index-order tuple at
     // every width from 16 to 512; neutral on small or uniform inputs).
     p.S = (cv > 1.5 && d_max > 256.0) ? 1 : 0;
-    p.SG = p.S ? 32 : 0;
+    p.SG = p.S ? (K >= 256 ? 32 : 64) : 0;
     p.omega = 64;
     if (p.S) p.flags |= PCSR_FLAG_COLUMN_ORDER;
     // Vector size 2 (Section 3.1) when adjacent rows share columns, and for short rows, where
@@ -671,10 +689,12 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.
     const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
-    // Balanced power-law inputs do best with four items per wavefront whatever K is and
-    // no repeats: 64-column slices (grid.y) cover wider rows, which also halves the bytes
-    // a cached B row occupies.
-    const int lpr_cap = p.S ? 16 : 64;
+    // Balanced power-law inputs do best without repeats and, once B outgrows the 256 MB
+    // memory-side cache, with 64-column slices (four items per wavefront; grid.y covers
+    // wider rows), which shrinks the bytes a cached B row occupies; a smaller B is gathered
+    // in 128-column slices.
+    const double b_bytes = f[0] * (double)K * 4.0;
+    const int lpr_cap = p.S ? (b_bytes > 192.0 * 1048576.0 ? 16 : 32) : 64;
     int lpr = 4;
     while (lpr * vec < K && lpr < lpr_cap) lpr <<= 1;
     int rep = 1;

@@ -300,45 +300,93 @@ int choose_windows(HostPcsr *hp, int32_t win_cols)
 {
     HostPcsr &h = *hp;
     h.win_cols = win_cols;
-    h.win_items = win_cols / 2;
+    h.win_ptr.clear();
     h.win_start.clear();
+    h.win_lo.clear();
+    h.win_hi.clear();
     h.win_hit = 0.0;
     if (win_cols <= 0) return PCSR_OK;
     try {
-        const int64_t nb = ceildiv(h.M, h.win_items);
-        h.win_start.assign(nb, -1);
-        std::vector<int64_t> hits(nb, 0);
-        parallel_for(nb, 16, [&](int64_t lo, int64_t hi) {
-            std::vector<int32_t> cols;
-            for (int64_t b = lo; b < hi; ++b) {
-                const int64_t i0 = b * h.win_items, i1 = std::min<int64_t>(h.M, i0 + h.win_items);
-                const int64_t s = h.rowptr[i0], e = h.rowptr[i1];
-                if (e <= s) continue;
-                cols.assign(h.colidx.begin() + s, h.colidx.begin() + e);
-                std::sort(cols.begin(), cols.end());
-                // densest window of win_cols columns: two pointers over the sorted columns
-                int64_t best = 0, best_lo = 0, l = 0;
-                for (int64_t r = 0; r < (int64_t)cols.size(); ++r) {
-                    while (cols[r] - cols[l] >= win_cols) ++l;
-                    if (r - l + 1 > best) {
-                        best = r - l + 1;
-                        best_lo = l;
-                    }
+        const int64_t M = h.M;
+        constexpr int64_t kProbe = 32; // items whose columns propose a block's window
+        // first column of the densest window of win_cols columns over items [i0, i1), and the
+        // vectors that fall inside it
+        std::vector<int32_t> cols;
+        auto densest = [&](int64_t i0, int64_t i1, int64_t *hits) -> int64_t {
+            const int64_t s = h.rowptr[i0], e = h.rowptr[i1];
+            *hits = 0;
+            if (e <= s) return -1;
+            cols.assign(h.colidx.begin() + s, h.colidx.begin() + e);
+            std::sort(cols.begin(), cols.end());
+            int64_t best = 0, best_lo = 0, l = 0;
+            for (int64_t r = 0; r < (int64_t)cols.size(); ++r) {
+                while (cols[r] - cols[l] >= win_cols) ++l;
+                if (r - l + 1 > best) {
+                    best = r - l + 1;
+                    best_lo = l;
                 }
-                // staging costs win_cols row reads: worth it from two uses per staged row
-                if (best >= 2 * (int64_t)win_cols) {
-                    int64_t c0 = cols[best_lo];
-                    c0 = std::min<int64_t>(c0, std::max<int64_t>(0, h.n_cols - win_cols));
-                    h.win_start[b] = (int32_t)c0;
-                    int64_t cnt = 0;
-                    for (int32_t c : cols) cnt += (c >= c0 && c < c0 + win_cols);
-                    hits[b] = cnt;
+            }
+            int64_t c0 = cols[best_lo];
+            c0 = std::min<int64_t>(c0, std::max<int64_t>(0, h.n_cols - win_cols));
+            int64_t cnt = 0;
+            for (int32_t c : cols) cnt += (c >= c0 && c < c0 + win_cols);
+            *hits = cnt;
+            return c0;
+        };
+        // A block grows item by item while the items keep gathering from the window its first
+        // kProbe items proposed (at least half of an item's vectors inside), up to win_cols
+        // items; where the matrix has no such structure blocks are kProbe items long.
+        int64_t total_hits = 0;
+        h.win_ptr.push_back(0);
+        for (int64_t i = 0; i < M;) {
+            const int64_t probe_end = std::min<int64_t>(M, i + kProbe);
+            int64_t hits = 0;
+            const int64_t c_probe = densest(i, probe_end, &hits);
+            int64_t j = probe_end;
+            if (c_probe >= 0) {
+                for (; j < M && j - i < win_cols; ++j) {
+                    const int64_t s = h.rowptr[j], e = h.rowptr[j + 1];
+                    if (e == s) continue;
+                    const int64_t in = std::lower_bound(h.colidx.begin() + s, h.colidx.begin() + e,
+                                                        (int32_t)std::min<int64_t>(c_probe + win_cols, INT32_MAX)) -
+                                       std::lower_bound(h.colidx.begin() + s, h.colidx.begin() + e, (int32_t)c_probe);
+                    if (2 * in < e - s) break;
+                }
+            }
+            // the block's own window; staging costs win_cols row reads, worth it from two
+            // uses per staged row
+            const int64_t c0 = densest(i, j, &hits);
+            if (c0 >= 0 && hits >= 2 * (int64_t)win_cols) {
+                h.win_start.push_back((int32_t)c0);
+                total_hits += hits;
+            } else {
+                h.win_start.push_back(-1);
+            }
+            h.win_ptr.push_back((int32_t)j);
+            i = j;
+        }
+        h.win_hit = h.nnz_v ? double(total_hits) / double(h.nnz_v) : 0.0;
+        // the run of every item that lies inside its block's window
+        h.win_lo.resize(M);
+        h.win_hi.resize(M);
+        const int64_t nb = (int64_t)h.win_start.size();
+        parallel_for(nb, 64, [&](int64_t b0, int64_t b1) {
+            for (int64_t b = b0; b < b1; ++b) {
+                const int64_t c0 = h.win_start[b];
+                for (int64_t it = h.win_ptr[b]; it < h.win_ptr[b + 1]; ++it) {
+                    const int64_t s = h.rowptr[it], e = h.rowptr[it + 1];
+                    if (c0 < 0) {
+                        h.win_lo[it] = h.win_hi[it] = (int32_t)s;
+                        continue;
+                    }
+                    const auto first = h.colidx.begin() + s, last = h.colidx.begin() + e;
+                    h.win_lo[it] = (int32_t)(std::lower_bound(first, last, (int32_t)c0) - h.colidx.begin());
+                    h.win_hi[it] = (int32_t)(std::lower_bound(first, last, (int32_t)std::min<int64_t>(
+                                                                               c0 + win_cols, INT32_MAX)) -
+                                             h.colidx.begin());
                 }
             }
         });
-        int64_t tot = 0;
-        for (int64_t v : hits) tot += v;
-        h.win_hit = h.nnz_v ? double(tot) / double(h.nnz_v) : 0.0;
         return PCSR_OK;
     } catch (const std::bad_alloc &) {
         return PCSR_E_OOM;

@@ -32,11 +32,15 @@ struct HostPcsr {
     // Not part of the format: item boundaries that cut the item sequence into 8 contiguous
     // ranges of equal work (vectors plus a per-item overhead), one per XCD.
     int32_t xcd_bounds[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-    // Column-window blocking (not part of the format): items are grouped win_items at a
-    // time; win_start[b] is the first column of block b's LDS-resident window, or -1
-    // when no window is worth staging for that block.
-    int32_t win_cols = 0, win_items = 0;
-    std::vector<int32_t> win_start;
+    // Column-window blocking (not part of the format): consecutive items are grouped into
+    // blocks [win_ptr[b], win_ptr[b+1]) of at most win_cols items that gather from the same
+    // stretch of columns; win_start[b] is the first column of block b's LDS-resident
+    // window, or -1 when no window is worth staging for that block.
+    int32_t win_cols = 0;
+    std::vector<int32_t> win_ptr, win_start;
+    // per item: its vectors [win_lo, win_hi) have their column inside the block's window
+    // (the columns of an item ascend, so they form one run)
+    std::vector<int32_t> win_lo, win_hi;
     double win_hit = 0.0; // fraction of nonzero vectors that fall inside their window
 };
 
@@ -54,8 +58,8 @@ int build_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
 // items in index order, both dealt to the 8 XCDs in contiguous equal-work slices.
 int schedule_by_column(HostPcsr *h);
 
-// Picks, per block of win_cols/2 consecutive items, the window of win_cols consecutive
-// columns holding most of the block's vectors (needs h->rowptr / h->colidx on the host).
+// Cuts the items into blocks that share a window of win_cols consecutive columns and picks
+// each block's window (needs h->rowptr / h->colidx on the host).
 int choose_windows(HostPcsr *h, int32_t win_cols);
 
 // Table 3 features in the order documented in pcsr.h.

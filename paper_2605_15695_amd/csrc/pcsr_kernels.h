@@ -30,9 +30,11 @@ struct SpmmArgs {
     // that runs there.  xb then bounds positions, not items.
     const int4 *sched;
     // column-window blocking (window kernel only)
+    const int32_t *win_ptr;   // item range [win_ptr[b], win_ptr[b+1]) of block b (= workgroup b)
     const int32_t *win_start; // per item block: first column of the staged window or -1
+    const int32_t *win_lo;    // per item: its vectors [win_lo, win_hi) lie inside the block's
+    const int32_t *win_hi;    // window (an empty range when the block has none)
     int32_t win_cols;         // rows of B staged in LDS
-    int32_t win_items;        // work items per block (= per workgroup)
     int32_t n_cols;
 };
 

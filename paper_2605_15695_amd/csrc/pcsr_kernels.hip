@@ -17,6 +17,9 @@
 #include "pcsr_kernels.h"
 
 #include <mutex>
+#include <type_traits>
+#include <set>
+#include <utility>
 
 // registers of B data a lane keeps in flight per gather step
 #ifndef PCSR_INFLIGHT
@@ -33,6 +36,12 @@
 // Workspace of the entry point that allocates nothing (pcsr_spmm_static).  In host code
 // this name is only a handle for hipGetSymbolAddress; kernels get the looked-up address.
 static __device__ __align__(256) unsigned char scratch[pcsr::kStaticScratchBytes];
+
+// Read in place of a row of B by the column-window kernel's memory gathers where an entry
+// slot past the end of a chunk, or a column past K, has nothing to load (an address select
+// instead of a branch around the load).  Indexed by column within the grid.y slice (at most
+// 64 lanes * 4 * 4 columns).
+static __device__ __align__(16) float g_zero_row[1024];
 
 namespace pcsr {
 namespace {
@@ -129,6 +138,76 @@ template <int LPR> __device__ __forceinline__ int bcast(int x, int j)
 template <int LPR> __device__ __forceinline__ float bcast(float x, int j)
 {
     return __int_as_float(bcast<LPR>(__float_as_int(x), j));
+}
+
+// Broadcast inside a 16-lane group when the source lane is known at compile time (the
+// unrolled step loop): a DPP move, "lane j of every row of 16 to the whole row", which runs
+// in the vector ALU instead of going through the LDS crossbar like ds_bpermute.
+__device__ __forceinline__ int bcast16_const(int x, int j)
+{
+#define PCSR_DPP_CASE(J) \
+    case J: return __builtin_amdgcn_update_dpp(0, x, 0x150 + J, 0xf, 0xf, false)
+    switch (j & 15) {
+        PCSR_DPP_CASE(0);
+        PCSR_DPP_CASE(1);
+        PCSR_DPP_CASE(2);
+        PCSR_DPP_CASE(3);
+        PCSR_DPP_CASE(4);
+        PCSR_DPP_CASE(5);
+        PCSR_DPP_CASE(6);
+        PCSR_DPP_CASE(7);
+        PCSR_DPP_CASE(8);
+        PCSR_DPP_CASE(9);
+        PCSR_DPP_CASE(10);
+        PCSR_DPP_CASE(11);
+        PCSR_DPP_CASE(12);
+        PCSR_DPP_CASE(13);
+        PCSR_DPP_CASE(14);
+    default: return __builtin_amdgcn_update_dpp(0, x, 0x150 + 15, 0xf, 0xf, false);
+    }
+#undef PCSR_DPP_CASE
+}
+// acc += (lane j of the 16-lane group's a) * b in one instruction: the DPP operand of a
+// VOP2 multiply-add does the broadcast, so no separate move is spent on it.
+__device__ __forceinline__ void fmac_bcast16_const(float &acc, float a, float b, int j)
+{
+#define PCSR_FMAC_CASE(J)                                                                             \
+    case J:                                                                                           \
+        asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:" #J " row_mask:0xf bank_mask:0xf"                 \
+            : "+v"(acc)                                                                               \
+            : "v"(a), "v"(b));                                                                        \
+        break
+    switch (j & 15) {
+        PCSR_FMAC_CASE(0);
+        PCSR_FMAC_CASE(1);
+        PCSR_FMAC_CASE(2);
+        PCSR_FMAC_CASE(3);
+        PCSR_FMAC_CASE(4);
+        PCSR_FMAC_CASE(5);
+        PCSR_FMAC_CASE(6);
+        PCSR_FMAC_CASE(7);
+        PCSR_FMAC_CASE(8);
+        PCSR_FMAC_CASE(9);
+        PCSR_FMAC_CASE(10);
+        PCSR_FMAC_CASE(11);
+        PCSR_FMAC_CASE(12);
+        PCSR_FMAC_CASE(13);
+        PCSR_FMAC_CASE(14);
+        PCSR_FMAC_CASE(15);
+    }
+#undef PCSR_FMAC_CASE
+}
+
+template <int LPR, bool CONST_LANE> __device__ __forceinline__ int bcast_any(int x, int j)
+{
+    if constexpr (LPR == 16 && CONST_LANE)
+        return bcast16_const(x, j);
+    else
+        return bcast<LPR>(x, j);
+}
+template <int LPR, bool CONST_LANE> __device__ __forceinline__ float bcast_any(float x, int j)
+{
+    return __int_as_float(bcast_any<LPR, CONST_LANE>(__float_as_int(x), j));
 }
 
 template <int V, bool S, int LPR, int VEC, int REP>
@@ -243,15 +322,18 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
 
         // U vectors per step: all broadcasts first, then all gathers, then the FMAs,
         // so U*REP loads are in flight together.  Slots past the end of the range
-        // carry val = 0 (set above) and load nothing.
-        for (int j = 0; j < cnt; j += U) {
+        // carry val = 0 (set above) and load nothing.  (Branching around those loads
+        // measured 1-3 % faster here than reading a row of zeros through an address select,
+        // although it costs more instructions: these kernels wait on memory.)
+        auto step = [&](int j, auto const_lane) {
+            constexpr bool CL = decltype(const_lane)::value;
             int cj[U];
             float aj[U][V];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                cj[u] = bcast<LPR>(c, j + u);
+                cj[u] = bcast_any<LPR, CL>(c, j + u);
 #pragma unroll
-                for (int v = 0; v < V; ++v) aj[u][v] = bcast<LPR>(av[v], j + u);
+                for (int v = 0; v < V; ++v) aj[u][v] = bcast_any<LPR, CL>(av[v], j + u);
             }
             float b[U][REP][VEC];
 #pragma unroll
@@ -277,6 +359,14 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
 #pragma unroll
                         for (int e = 0; e < VEC; ++e)
                             part[v][r][e] = fmaf(aj[u][v], b[u][r][e], part[v][r][e]);
+        };
+        if constexpr (LPR == 16) {
+            // the 16 / U steps written out, so every broadcast lane is a constant
+#pragma unroll
+            for (int j = 0; j < LPR; j += U)
+                if (j < cnt) step(j, std::true_type{});
+        } else {
+            for (int j = 0; j < cnt; j += U) step(j, std::false_type{});
         }
 #pragma unroll
         for (int v = 0; v < V; ++v)
@@ -460,12 +550,17 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
     }
 }
 
-// Column-window kernel (no balancing): one workgroup owns a block of win_items consecutive
-// work items and one grid.y column slice.  It first copies rows [c0, c0 + win_cols) of
+// Column-window kernel (no balancing): one workgroup owns a block of consecutive work items
+// (cut at build time where the rows move on to other columns) and one grid.y column slice.  It first copies rows [c0, c0 + win_cols) of
 // that B slice into LDS (c0 chosen at build time as the densest window of the block's
 // columns), then walks its items like spmm_kernel, taking each B segment from LDS when
 // the column falls inside the window and from memory otherwise.  On clustered matrices
-// most gathers then cost LDS bandwidth instead of L1/L2 bandwidth.
+// most gathers then cost LDS bandwidth instead of L2 round trips: a compute unit can only
+// keep a few hundred cache lines in flight, which caps L2-resident gathers near 23 TB/s
+// on the whole chip, while its LDS delivers 128 bytes per clock.
+// Everything that would put a memory round trip into the walk is requested one step ahead:
+// the next item's vector range while the current item is processed, the next chunk of
+// colIdx/val while the current chunk's rows are read.
 template <int V, int LPR, int VEC, int REP>
 __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
 {
@@ -490,24 +585,35 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
     const float *__restrict__ B = a.B;
     const long K = a.K;
 
+    const int item_begin = a.win_ptr[bid];
+    const int item_end = a.win_ptr[bid + 1];
+    const int stride = waves * G;
+    int item = item_begin + wave * G + lane / LPR;
+    // the first item's ranges are requested before the window is staged
+    int head = 0, tail = 0, lo = 0, hi = 0;
+    if (item < item_end) {
+        head = a.rowptr[item];
+        tail = a.rowptr[item + 1];
+        lo = a.win_lo[item];
+        hi = a.win_hi[item];
+    }
+
     const int c0 = a.win_start[bid];
-    const bool has_win = c0 >= 0;
-    if (has_win) { // uniform over the workgroup
+    if (c0 >= 0) { // uniform over the workgroup
         constexpr int VPR = TW / VEC; // vector loads per staged row
-        const int total = a.win_cols * VPR;
+        const int total = (a.win_cols + 1) * VPR; // the window, then one row of zeros
         for (int q = tid; q < total; q += blockDim.x) {
             const int r = q / VPR;
             const int e = (q - r * VPR) * VEC;
             const int col = c0 + r;
             float t[VEC];
-            if (col < a.n_cols && kbase + e < a.K) {
+            if (r < a.win_cols && col < a.n_cols && kbase + e < a.K) {
                 load_vec<VEC>(B + (long)col * K + kbase + e, t);
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) t[i] = 0.0f;
             }
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) lds[r * LW + e + i] = t[i];
+            store_vec_cached<VEC>(lds + r * LW + e, t);
         }
         __syncthreads();
     }
@@ -520,15 +626,17 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
         kv[r] = kbase + kl[r] < a.K;
     }
 
-    const int item_begin = bid * a.win_items;
-    const int item_end = min(a.M, item_begin + a.win_items);
-    for (int item = item_begin + wave * G + lane / LPR; item < item_end; item += waves * G) {
-        int head = a.rowptr[item];
-        int tail = a.rowptr[item + 1];
-        if constexpr (LPR == 64) {
-            head = __builtin_amdgcn_readfirstlane(head);
-            tail = __builtin_amdgcn_readfirstlane(tail);
+    while (item < item_end) {
+        // ranges of the item this group takes next
+        const int item_next = item + stride;
+        int head_next = 0, tail_next = 0, lo_next = 0, hi_next = 0;
+        if (item_next < item_end) {
+            head_next = a.rowptr[item_next];
+            tail_next = a.rowptr[item_next + 1];
+            lo_next = a.win_lo[item_next];
+            hi_next = a.win_hi[item_next];
         }
+
         float acc[V][REP][VEC];
 #pragma unroll
         for (int v = 0; v < V; ++v)
@@ -537,81 +645,121 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) acc[v][r][e] = 0.0f;
 
-        for (int base = head; base < tail; base += LPR) {
-            const int idx = base + lg;
-            int c = 0;
-            float av[V];
+        // Walks the n vectors whose i-th member is vector first + i (i < n1) or
+        // second + (i - n1): one contiguous run, or two runs taken as one.  The columns of an
+        // item ascend, so the vectors inside the window are one run [lo, hi) and the others
+        // the two runs around it; each kind is walked on its own, the memory gathers with
+        // several loads in flight and no LDS access in between, the LDS reads with no memory
+        // round trip in between.
+        auto walk = [&](int first, int n1, int second, int n, auto from_lds) {
+            constexpr bool LDS = decltype(from_lds)::value;
+            auto load_entry = [&](int i0, int &c, float (&av)[V]) {
+                const int i = i0 + lg;
+                c = 0;
 #pragma unroll
-            for (int v = 0; v < V; ++v) av[v] = 0.0f;
-            if (idx < tail) {
-                c = stream_load(a.colidx + idx);
-                if constexpr (V == 1) {
-                    av[0] = stream_load(a.val + idx);
-                } else {
-                    typedef float f2 __attribute__((ext_vector_type(2)));
-                    const f2 t = stream_load(reinterpret_cast<const f2 *>(a.val) + idx);
-                    av[0] = t[0];
-                    av[1] = t[1];
-                }
-            }
-            const int cnt = min(LPR, tail - base);
-            float part[V][REP][VEC];
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-#pragma unroll
-                for (int r = 0; r < REP; ++r)
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) part[v][r][e] = 0.0f;
-
-            for (int j = 0; j < cnt; j += U) {
-                int cj[U];
-                float aj[U][V];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    cj[u] = bcast<LPR>(c, j + u);
-#pragma unroll
-                    for (int v = 0; v < V; ++v) aj[u][v] = bcast<LPR>(av[v], j + u);
-                }
-                float b[U][REP][VEC];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const bool ok = j + u < cnt;
-                    const unsigned off = (unsigned)(cj[u] - c0);
-                    const bool inw = has_win && off < (unsigned)a.win_cols;
-                    const float *brow = B + (long)cj[u] * K + kbase;
-                    const float *lrow = lds + off * LW;
-#pragma unroll
-                    for (int r = 0; r < REP; ++r) {
-                        if (ok && kv[r]) {
-                            if (inw) {
-#pragma unroll
-                                for (int e = 0; e < VEC; ++e) b[u][r][e] = lrow[kl[r] + e];
-                            } else {
-                                load_vec<VEC>(brow + kl[r], b[u][r]);
-                            }
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < VEC; ++e) b[u][r][e] = 0.0f;
-                        }
+                for (int v = 0; v < V; ++v) av[v] = 0.0f;
+                if (i < n) {
+                    const int idx = i < n1 ? first + i : second + (i - n1);
+                    c = stream_load(a.colidx + idx);
+                    if constexpr (V == 1) {
+                        av[0] = stream_load(a.val + idx);
+                    } else {
+                        typedef float f2 __attribute__((ext_vector_type(2)));
+                        const f2 t = stream_load(reinterpret_cast<const f2 *>(a.val) + idx);
+                        av[0] = t[0];
+                        av[1] = t[1];
                     }
                 }
+            };
+            int c_next;
+            float av_next[V];
+            load_entry(0, c_next, av_next);
+            for (int base = 0; base < n; base += LPR) {
+                const int c = c_next;
+                float av[V];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
+                for (int v = 0; v < V; ++v) av[v] = av_next[v];
+                load_entry(base + LPR, c_next, av_next);
+                const int cnt = min(LPR, n - base);
+                // where this lane's entry sits in the staged window (floats from lds); a slot
+                // past the end of the run reads the row of zeros staged after the window
+                const int loff = LDS ? (base + lg < n ? c - c0 : a.win_cols) * LW : 0;
+                float part[V][REP][VEC];
+#pragma unroll
+                for (int v = 0; v < V; ++v)
 #pragma unroll
                     for (int r = 0; r < REP; ++r)
 #pragma unroll
-                        for (int v = 0; v < V; ++v)
+                        for (int e = 0; e < VEC; ++e) part[v][r][e] = 0.0f;
+
+                auto step = [&](int j, auto const_lane) {
+                    constexpr bool CL = decltype(const_lane)::value;
+                    // LDS reads of a 16-lane group with constant source lanes: the broadcast of
+                    // the value rides on the multiply-add, and the row's LDS offset was
+                    // computed once by the lane that holds the entry
+                    constexpr bool FUSED = LDS && CL && LPR == 16;
+                    int cj[U];
+                    float aj[U][V];
 #pragma unroll
-                            for (int e = 0; e < VEC; ++e)
-                                part[v][r][e] = fmaf(aj[u][v], b[u][r][e], part[v][r][e]);
+                    for (int u = 0; u < U; ++u) {
+                        cj[u] = bcast_any<LPR, CL>(LDS ? loff : c, j + u);
+                        if constexpr (!FUSED) {
+#pragma unroll
+                            for (int v = 0; v < V; ++v) aj[u][v] = bcast_any<LPR, CL>(av[v], j + u);
+                        }
+                    }
+                    float b[U][REP][VEC];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+#pragma unroll
+                        for (int r = 0; r < REP; ++r) {
+                            if constexpr (LDS) {
+                                // one ds_read of VEC floats, never predicated: slots past the
+                                // end point at the zero row, columns past K were staged as zeros
+                                load_vec<VEC>(lds + cj[u] + kl[r], b[u][r]);
+                            } else {
+                                const bool ok = j + u < cnt;
+                                const float *src = (ok && kv[r]) ? B + (long)cj[u] * K + kbase + kl[r]
+                                                                 : g_zero_row + kl[r];
+                                load_vec<VEC>(src, b[u][r]);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int r = 0; r < REP; ++r)
+#pragma unroll
+                            for (int v = 0; v < V; ++v)
+#pragma unroll
+                                for (int e = 0; e < VEC; ++e) {
+                                    if constexpr (FUSED)
+                                        fmac_bcast16_const(part[v][r][e], av[v], b[u][r][e], j + u);
+                                    else
+                                        part[v][r][e] = fmaf(aj[u][v], b[u][r][e], part[v][r][e]);
+                                }
+                };
+                if constexpr (LPR == 16) {
+#pragma unroll
+                    for (int j = 0; j < LPR; j += U)
+                        if (j < cnt) step(j, std::true_type{});
+                } else {
+                    for (int j = 0; j < cnt; j += U) step(j, std::false_type{});
+                }
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+#pragma unroll
+                    for (int r = 0; r < REP; ++r)
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) acc[v][r][e] += part[v][r][e];
             }
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-#pragma unroll
-                for (int r = 0; r < REP; ++r)
-#pragma unroll
-                    for (int e = 0; e < VEC; ++e) acc[v][r][e] += part[v][r][e];
-        }
+        };
+#ifndef PCSR_WIN_SKIP_GLOBAL /* timing experiments only: the result is wrong without either walk */
+        walk(head, lo - head, hi, (lo - head) + (tail - hi), std::false_type{}); // outside the window
+#endif
+#ifndef PCSR_WIN_SKIP_LDS
+        walk(lo, hi - lo, lo, hi - lo, std::true_type{});                        // inside: from LDS
+#endif
 
 #pragma unroll
         for (int v = 0; v < V; ++v) {
@@ -623,6 +771,11 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
                     if (kv[r]) store_vec<VEC>(crow + kl[r], acc[v][r]);
             }
         }
+        item = item_next;
+        head = head_next;
+        tail = tail_next;
+        lo = lo_next;
+        hi = hi_next;
     }
 }
 
@@ -825,10 +978,24 @@ hipError_t launch_spmm(int V, int S, const LaunchShape &ls, const SpmmArgs &args
     if (ls.window) {
         KernelFn fn = S ? nullptr : pick_window(V, ls.lpr, ls.vec, ls.rep);
         if (!fn) return hipErrorInvalidValue;
-        // more than 64 KiB of dynamic LDS has to be allowed per kernel function
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, ls.lds_bytes);
-        if (e != hipSuccess) return e;
+        // More than 64 KiB of dynamic LDS has to be allowed per kernel function: raised to
+        // the 160 KiB of the CU once per function and device, not on every launch (the
+        // call is host work and is not capturable in a HIP graph).
+        {
+            static std::mutex mu;
+            static std::set<std::pair<int, const void *>> raised;
+            int dev = -1;
+            hipError_t e = hipGetDevice(&dev);
+            if (e != hipSuccess) return e;
+            std::lock_guard<std::mutex> lock(mu);
+            const auto key = std::make_pair(dev, reinterpret_cast<const void *>(fn));
+            if (!raised.count(key)) {
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(fn),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) return e;
+                raised.insert(key);
+            }
+        }
         hipLaunchKernelGGL(fn, dim3(ls.grid_x, ls.grid_y), dim3(64 * ls.waves), ls.lds_bytes, stream, args);
         return hipGetLastError();
     }

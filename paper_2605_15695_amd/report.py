@@ -12,14 +12,47 @@ import math
 import sys
 
 
+def records_table(recs) -> None:
+    """Compact view of the recorded sweep: per input, the best median time of every format tuple
+    (over launch shapes) and of every launch shape (over formats), relative to the input's best."""
+    keys = sorted({(r["workload"], r["K"]) for r in recs if r.get("kind") == "pcsr"})
+    fmt_name = lambda r: (f'V{r["V"]} S{r["S"]} SG{r["SG"]}' + (" col-order" if r.get("build_flags", 0) & 64 else "")
+                          + (f' window{r["col_window"]}' if r.get("col_window") else ""))
+    shape_name = lambda r: (f'{r["lanes_per_row"]}x{r["vec"]}x{r["rep"]} w{r["waves_per_wg"]}'
+                            + (f' i{r["items_per_group"]}' if r.get("items_per_group", 1) > 1 else ""))
+    for w, K in keys:
+        rs = [r for r in recs if r.get("kind") == "pcsr" and r["workload"] == w and r["K"] == K]
+        best = min(r["ms_median"] for r in rs)
+        print(f"\n### {w}, K={K}: best {best:.4f} ms over {len(rs)} timed tuples\n")
+        for title, name in (("format (V, S, SG)", fmt_name), ("launch shape (lanes x vec x rep, waves)", shape_name)):
+            by = {}
+            for r in rs:
+                k = name(r)
+                if k not in by or r["ms_median"] < by[k]["ms_median"]:
+                    by[k] = r
+            rows = sorted(by.items(), key=lambda kv: kv[1]["ms_median"])[:10]
+            print(f"| {title} | best ms | % of input's best | reached with |")
+            print("|---|---|---|---|")
+            for k, r in rows:
+                other = shape_name(r) if name is fmt_name else fmt_name(r)
+                print(f'| {k} | {r["ms_median"]:.4f} | {100 * best / r["ms_median"]:.0f} | {other} |')
+            print()
+
+
 def main(argv=None) -> int:
-    paths = (argv or sys.argv[1:])
+    paths = list(argv or sys.argv[1:])
+    records = "--records" in paths
+    if records:
+        paths.remove("--records")
     recs = []
     for p in paths:
         with open(p) as f:
             recs += [json.loads(line) for line in f if line.strip()]
+    if records:
+        records_table(recs)
+        return 0
     keys = sorted({(r["workload"], r["K"]) for r in recs if r.get("kind") == "pcsr"})
-    print("| workload | K | n | nnz | best tuple (V,S,SG / lanes,vec,rep,waves,items) | ms | GFLOP/s | roofline frac "
+    print("| workload | K | n | nnz | best tuple (V,S,SG[c = column-ordered] / lanes,vec,rep,waves,items) | ms | GFLOP/s | roofline frac "
           "| gather TB/s | selected ms (% of best) | hipSPARSE best ms | speed-up | Alg. 1 ms |")
     print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     ratios, sel_ratios, rnd_ratios, at_half = [], [], [], 0
@@ -33,8 +66,8 @@ def main(argv=None) -> int:
         a1 = [r["ms_median"] for r in recs if r.get("kind") == "alg1" and r["workload"] == w and r["K"] == K]
         a1_txt = f"{min(a1):.4f}" if a1 else "-"
         s = min(sel, key=lambda r: r["ms_median"]) if sel else None
-        tup = (f'{b["V"]},{b["S"]},{b["SG"]} / {b["lanes_per_row"]},{b["vec"]},{b["rep"]},'
-               f'{b["waves_per_wg"]},{b.get("items_per_group", 1)}')
+        tup = (f'{b["V"]},{b["S"]},{b["SG"]}{"c" if b.get("build_flags", 0) & 64 else ""} / '
+               f'{b["lanes_per_row"]},{b["vec"]},{b["rep"]},{b["waves_per_wg"]},{b.get("items_per_group", 1)}')
         gather = b["nnz"] * K * 4 / (b["ms_median"] * 1e-3) / 1e12
         # ratio against the best tuple re-timed next to the pick when the sweep recorded it
         sref = (s.get("best_retimed_ms") or b["ms_median"]) if s else None

@@ -93,8 +93,8 @@ def main(argv=None) -> int:
     ap.add_argument("--K", type=int, nargs="*", default=None)
     ap.add_argument("--out", required=True)
     ap.add_argument("--quick", action="store_true", help="widest vector only, waves in {2,4}")
-    ap.add_argument("--reps", type=int, default=8)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--reps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--formats", default="all",
                     help="all | comma list of V:S:SG[:col_window[:flags]], e.g. 1:0:0,1:1:64,1:1:64:0:64 "
                          "(flags: PCSR_FLAG_* bits given to pcsr_build, 64 = column-ordered schedule)")
@@ -141,8 +141,9 @@ def main(argv=None) -> int:
 
     if args.formats == "all":
         sg_eq3 = 0
-        formats = [(1, 0, 0), (2, 0, 0), (1, 1, sg_eq3), (2, 1, sg_eq3), (1, 1, 256), (1, 1, 1024),
-                   (1, 0, 0, 512), (1, 0, 0, 1024)]
+        co = pc.PCSR_FLAG_COLUMN_ORDER
+        formats = [(1, 0, 0), (2, 0, 0), (1, 1, sg_eq3), (2, 1, sg_eq3), (1, 1, 256), (1, 1, 1024), (2, 1, 1024),
+                   (1, 1, 32, 0, co), (1, 1, 64, 0, co), (2, 1, 64, 0, co), (1, 0, 0, 512), (1, 0, 0, 1024)]
     else:
         formats = [tuple(int(x) for x in f.split(":")) for f in args.formats.split(",")]
     formats = [f + (0,) * (5 - len(f)) for f in formats]             # (V, S, SG, col_window, build flags)
