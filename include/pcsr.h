@@ -51,6 +51,11 @@ enum {
                                   so that the wavefronts of one XCD gather the same rows of B
                                   at about the same time; all other items run in index order.
                                   The PCSR arrays do not change                                */
+    PCSR_FLAG_WINDOW_IF_USEFUL = 128, /* with col_window: keep the window blocks only if the build
+                                  finds the structure they need (at least half of the nonzero
+                                  vectors inside their block's window and blocks of 128 items or
+                                  more on average); otherwise the handle is built as if
+                                  col_window were 0 and its kernel parameters are set to auto */
     PCSR_FLAG_ATOMIC_SPLIT = 32 /* S = 1 only: panels that were split accumulate into C with
                                   fp32 atomics, as Algorithm 2 prints it, instead of the
                                   default two-pass write-back (see pcsr_spmm)                 */
@@ -228,11 +233,13 @@ int pcsr_export_schedule(pcsr_handle_t h, int64_t *n_positions, int32_t *sched, 
 /*
  * Sparse-matrix features of Table 3, in this order (host, fp64[PCSR_N_FEATURES]):
  *   n, n_hat, nnz, delta, d, d_hat, d_max, CV, CV_hat, SR_1, SR_2, rho, b, b_max,
- *   PR_1, PR_2      (SR: Eq. (4) under S with Eq. (3)'s SG; PR: Eq. (2)).
+ *   PR_1, PR_2      (SR: Eq. (4) under S with Eq. (3)'s SG; PR: Eq. (2)),
+ * followed by one feature that is not in the paper:
+ *   near_512        share of the nonzeros with |column - row| < 512 (0 for nnz = 0).
  * rowptr/colidx: host.  omega as in pcsr_params_t (0 = 64).
  * Errors: INVALID_ARG (n_out < PCSR_N_FEATURES, nulls), BAD_CSR.
  */
-#define PCSR_N_FEATURES 16
+#define PCSR_N_FEATURES 17
 int pcsr_features(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
                   const int32_t *colidx, int32_t omega, double *out, int32_t n_out);
 

@@ -20,9 +20,10 @@ PCSR_FLAG_DEVICE_CSR, PCSR_FLAG_NO_VALIDATE, PCSR_FLAG_NO_XCD_REMAP, PCSR_FLAG_H
 PCSR_FLAG_GPU_BUILD = 16
 PCSR_FLAG_ATOMIC_SPLIT = 32
 PCSR_FLAG_COLUMN_ORDER = 64
-PCSR_N_FEATURES = 16
+PCSR_FLAG_WINDOW_IF_USEFUL = 128
+PCSR_N_FEATURES = 17
 FEATURE_NAMES = ("n", "n_hat", "nnz", "delta", "d", "d_hat", "d_max", "CV", "CV_hat",
-                 "SR_1", "SR_2", "rho", "b", "b_max", "PR_1", "PR_2")
+                 "SR_1", "SR_2", "rho", "b", "b_max", "PR_1", "PR_2", "near_512")
 
 
 class pcsr_params_t(ctypes.Structure):

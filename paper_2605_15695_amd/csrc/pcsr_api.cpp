@@ -351,6 +351,18 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
         h->waves = prm.waves_per_wg;
         h->ipg = prm.items_per_group;
         h->flags = prm.flags;
+        if (prm.col_window && (prm.flags & PCSR_FLAG_WINDOW_IF_USEFUL) &&
+            (h->host.win_hit < 0.5 || h->host.M < 128 * h->n_win_blocks)) {
+            // no structure for the window kernel to use: an ordinary handle
+            h->host.win_cols = 0;
+            h->host.win_hit = 0.0;
+            h->n_win_blocks = 0;
+            std::vector<int32_t>().swap(h->host.win_start);
+            std::vector<int32_t>().swap(h->host.win_ptr);
+            std::vector<int32_t>().swap(h->host.win_lo);
+            std::vector<int32_t>().swap(h->host.win_hi);
+            h->lpr = h->vec = h->rep = h->waves = h->ipg = 0;
+        }
         h->n_split = (int64_t)h->host.split_panels.size();
         h->n_split_items = h->host.split_slot.empty() ? 0 : h->host.split_slot.back();
         if (!host_only) {
@@ -711,6 +723,20 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     p.waves_per_wg = p.S ? 4 : (d_hat >= 16.0 ? 8 : 2);
     p.items_per_group = 1;
     p.col_window = 0;
+    // Column-window blocking: rows that gather from a neighbourhood of their own index (most
+    // nonzeros within 512 columns of the diagonal) and are long enough that every staged row
+    // of B is used dozens of times.  A 500-node community graph of degree 48 runs 1.1x
+    // (K = 32) to 1.4x (K = 512) faster from LDS than from L2; cliques of 25 or blocks of 50
+    // nodes do not repay the staging.  The build drops the window again if the blocks it
+    // finds are poor.
+    if (!p.S && f[16] >= 0.6 && d_hat >= 40.0 && vec == 4) {
+        p.V = 1;
+        p.col_window = 512;
+        p.flags |= PCSR_FLAG_WINDOW_IF_USEFUL;
+        p.lanes_per_row = K >= 64 ? 16 : 8; // 64-column slices of the window (136 KiB of LDS)
+        p.rep = 1;
+        p.waves_per_wg = K >= 64 ? 16 : 8;
+    }
     *out = p;
     return PCSR_OK;
 }

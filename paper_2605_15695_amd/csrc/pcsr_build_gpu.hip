@@ -273,7 +273,7 @@ __global__ void xcd_bounds_kernel(int32_t M, const int32_t *rowptr, int32_t *xb)
 
 // ---- Table 3 features on the GPU (two passes over the row pointer, one over colIdx)
 struct FeatAcc {
-    unsigned long long n_hat, nnz2, nonempty2, M1, M2;
+    unsigned long long n_hat, nnz2, nonempty2, M1, M2, near;
     int d_max;
     int pad;
     double bw_sum, bw_max, ss, ss_hat;
@@ -296,7 +296,7 @@ __global__ void features_pass1_kernel(int64_t n_rows, const int32_t *rowptr, con
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int nh = 0, dmax = 0, ne2 = 0;
-    long l2 = 0;
+    long l2 = 0, near = 0;
     double bw = 0.0;
     if (i < n_rows) {
         const int64_t s = rowptr[i], e = rowptr[i + 1];
@@ -305,6 +305,19 @@ __global__ void features_pass1_kernel(int64_t n_rows, const int32_t *rowptr, con
             nh = 1;
             dmax = l;
             bw = (double)colidx[e - 1] - (double)colidx[s];
+            // nonzeros with |column - row| < 512: two binary searches in the ascending row
+            auto lower = [&](int64_t key) {
+                int64_t lo = s, hi = e;
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) / 2;
+                    if (colidx[mid] < key)
+                        lo = mid + 1;
+                    else
+                        hi = mid;
+                }
+                return lo;
+            };
+            near = lower(i + 512) - lower(i - 511);
         }
         if ((i & 1) == 0) {
             int64_t a = s, ae = e, b = e, be = (i + 1 < n_rows) ? rowptr[i + 2] : e, n = 0;
@@ -331,6 +344,8 @@ __global__ void features_pass1_kernel(int64_t n_rows, const int32_t *rowptr, con
     __syncthreads();
     const int s_ne2 = RI(ti).Sum(ne2);
     const long s_l2 = RL(tl).Sum(l2);
+    __syncthreads();
+    const long s_near = RL(tl).Sum(near);
     const double s_bw = RD(td).Sum(bw);
     __syncthreads();
     const double m_bw = RD(td).Reduce(bw, hipcub::Max());
@@ -339,6 +354,7 @@ __global__ void features_pass1_kernel(int64_t n_rows, const int32_t *rowptr, con
         if (s_dmax) atomicMax(&acc->d_max, s_dmax);
         if (s_ne2) atomicAdd(&acc->nonempty2, (unsigned long long)s_ne2);
         if (s_l2) atomicAdd(&acc->nnz2, (unsigned long long)s_l2);
+        if (s_near) atomicAdd(&acc->near, (unsigned long long)s_near);
         if (s_bw != 0.0) atomicAdd(&acc->bw_sum, s_bw);
         if (m_bw > 0.0) atomic_max_double(&acc->bw_max, m_bw);
     }
@@ -738,6 +754,7 @@ int features_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *
     out[13] = h.bw_max;
     out[14] = 0.0;
     out[15] = h.nnz2 ? 1.0 - double(nnz) / (double(h.nnz2) * 2.0) : 0.0;
+    out[16] = nnz ? double(h.near) / double(nnz) : 0.0;
     return PCSR_OK;
 }
 

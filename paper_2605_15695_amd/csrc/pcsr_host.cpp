@@ -453,6 +453,21 @@ int features_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *ro
     out[13] = bw_max;
     out[14] = 0.0;
     out[15] = nnz2 ? 1.0 - double(nnz) / (double(nnz2) * 2.0) : 0.0;
+    // Own addition to Table 3: the share of nonzeros within 512 columns of the diagonal
+    // (columns ascend inside a row, so two binary searches per row count them).  High for
+    // matrices whose rows gather from a neighbourhood of their own index, the case the
+    // column-window kernel is for.
+    std::atomic<int64_t> near{0};
+    parallel_for(n_rows, 1 << 14, [&](int64_t lo, int64_t hi) {
+        int64_t cnt = 0;
+        for (int64_t i = lo; i < hi; ++i) {
+            const int32_t *first = colidx + rowptr[i], *last = colidx + rowptr[i + 1];
+            const int64_t c_lo = std::max<int64_t>(i - 511, 0), c_hi = std::min<int64_t>(i + 512, INT32_MAX);
+            cnt += std::lower_bound(first, last, (int32_t)c_hi) - std::lower_bound(first, last, (int32_t)c_lo);
+        }
+        near += cnt;
+    });
+    out[16] = nnz ? double(near.load()) / double(nnz) : 0.0;
     return PCSR_OK;
 }
 

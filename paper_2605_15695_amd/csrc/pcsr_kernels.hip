@@ -216,7 +216,8 @@ __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
     constexpr int G = 64 / LPR;
     // vectors gathered per inner step: about 16 registers of B data in flight
     constexpr int U0 = (S ? PCSR_INFLIGHT_SPLIT : PCSR_INFLIGHT) / (REP * VEC);
-    constexpr int U = U0 < 1 ? 1 : (U0 > PCSR_MAXSTEP ? PCSR_MAXSTEP : (U0 > LPR ? LPR : U0));
+    constexpr int Uc = U0 < 1 ? 1 : (U0 > PCSR_MAXSTEP ? PCSR_MAXSTEP : U0);
+    constexpr int U = Uc > LPR ? LPR : Uc; // a step never reaches past the group's chunk
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int waves = blockDim.x >> 6;
@@ -424,7 +425,8 @@ __global__ void __launch_bounds__(512) spmm_batched_kernel(SpmmArgs a)
     static_assert(IPG < LPR, "item boundaries are broadcast from the group's own lanes");
     constexpr int G = 64 / LPR;
     constexpr int U0 = PCSR_INFLIGHT / (REP * VEC);
-    constexpr int U = U0 < 1 ? 1 : (U0 > 8 ? 8 : (U0 > LPR ? LPR : U0));
+    constexpr int Uc = U0 < 1 ? 1 : (U0 > 8 ? 8 : U0);
+    constexpr int U = Uc > LPR ? LPR : Uc; // a step never reaches past the group's chunk
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int waves = blockDim.x >> 6;
@@ -568,8 +570,16 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
     constexpr int G = 64 / LPR;
     constexpr int TW = LPR * VEC * REP; // columns per slice
     constexpr int LW = TW + 4;          // floats per staged row, padded so rows start on different banks
-    constexpr int U0 = PCSR_INFLIGHT / (REP * VEC);
-    constexpr int U = U0 < 1 ? 1 : (U0 > 8 ? 8 : (U0 > LPR ? LPR : U0));
+    // Vectors per step.  The LDS window caps a compute unit at one or two workgroups, so a
+    // wavefront may use many registers: memory gathers go 64 registers deep (the few
+    // out-of-window vectors of an item then cost one round trip), LDS reads 32.
+    constexpr int UG0 = 64 / (REP * VEC), UL0 = 32 / (REP * VEC);
+    constexpr int UGc = UG0 < 1 ? 1 : (UG0 > 16 ? 16 : UG0), ULc = UL0 < 1 ? 1 : (UL0 > 16 ? 16 : UL0);
+    constexpr int UG = UGc > LPR ? LPR : UGc; // a step never reaches past the group's chunk
+    constexpr int UL = ULc > LPR ? LPR : ULc;
+    // out-of-window vectors of an item whose gathers are issued before its LDS walk and used
+    // after it (32 registers held across the walk)
+    constexpr int UP = UL;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -615,7 +625,6 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
             }
             store_vec_cached<VEC>(lds + r * LW + e, t);
         }
-        __syncthreads();
     }
 
     int kl[REP]; // column offset inside the slice
@@ -625,6 +634,34 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
         kl[r] = (r * LPR + lg) * VEC;
         kv[r] = kbase + kl[r] < a.K;
     }
+
+    // This lane's entry of the chunk that starts at member i0 of a walk: the walk's i-th
+    // member is vector first + i (i < n1) or second + (i - n1); zeros past its n members.
+    auto load_entry = [&](int first, int n1, int second, int n, int i0, int &c, float (&av)[V]) {
+        const int i = i0 + lg;
+        c = 0;
+#pragma unroll
+        for (int v = 0; v < V; ++v) av[v] = 0.0f;
+        if (i < n) {
+            const int idx = i < n1 ? first + i : second + (i - n1);
+            c = stream_load(a.colidx + idx);
+            if constexpr (V == 1) {
+                av[0] = stream_load(a.val + idx);
+            } else {
+                typedef float f2 __attribute__((ext_vector_type(2)));
+                const f2 t = stream_load(reinterpret_cast<const f2 *>(a.val) + idx);
+                av[0] = t[0];
+                av[1] = t[1];
+            }
+        }
+    };
+    // first chunk of both walks of the current item, requested while the previous item was
+    // still being processed (here: before the window is complete)
+    int cg0, cl0;
+    float avg0[V], avl0[V];
+    load_entry(head, lo - head, hi, (lo - head) + (tail - hi), 0, cg0, avg0);
+    load_entry(lo, hi - lo, lo, hi - lo, 0, cl0, avl0);
+    if (c0 >= 0) __syncthreads(); // the staged window is complete (uniform over the workgroup)
 
     while (item < item_end) {
         // ranges of the item this group takes next
@@ -651,35 +688,20 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
         // the two runs around it; each kind is walked on its own, the memory gathers with
         // several loads in flight and no LDS access in between, the LDS reads with no memory
         // round trip in between.
-        auto walk = [&](int first, int n1, int second, int n, auto from_lds) {
+        auto walk = [&](int first, int n1, int second, int n, int i_start, int c_first,
+                        const float (&av_first)[V], auto from_lds) {
             constexpr bool LDS = decltype(from_lds)::value;
-            auto load_entry = [&](int i0, int &c, float (&av)[V]) {
-                const int i = i0 + lg;
-                c = 0;
-#pragma unroll
-                for (int v = 0; v < V; ++v) av[v] = 0.0f;
-                if (i < n) {
-                    const int idx = i < n1 ? first + i : second + (i - n1);
-                    c = stream_load(a.colidx + idx);
-                    if constexpr (V == 1) {
-                        av[0] = stream_load(a.val + idx);
-                    } else {
-                        typedef float f2 __attribute__((ext_vector_type(2)));
-                        const f2 t = stream_load(reinterpret_cast<const f2 *>(a.val) + idx);
-                        av[0] = t[0];
-                        av[1] = t[1];
-                    }
-                }
-            };
-            int c_next;
+            constexpr int U = LDS ? UL : UG;
+            int c_next = c_first;
             float av_next[V];
-            load_entry(0, c_next, av_next);
-            for (int base = 0; base < n; base += LPR) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) av_next[v] = av_first[v];
+            for (int base = i_start; base < n; base += LPR) {
                 const int c = c_next;
                 float av[V];
 #pragma unroll
                 for (int v = 0; v < V; ++v) av[v] = av_next[v];
-                load_entry(base + LPR, c_next, av_next);
+                load_entry(first, n1, second, n, base + LPR, c_next, av_next);
                 const int cnt = min(LPR, n - base);
                 // where this lane's entry sits in the staged window (floats from lds); a slot
                 // past the end of the run reads the row of zeros staged after the window
@@ -754,12 +776,49 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
                         for (int e = 0; e < VEC; ++e) acc[v][r][e] += part[v][r][e];
             }
         };
-#ifndef PCSR_WIN_SKIP_GLOBAL /* timing experiments only: the result is wrong without either walk */
-        walk(head, lo - head, hi, (lo - head) + (tail - hi), std::false_type{}); // outside the window
-#endif
-#ifndef PCSR_WIN_SKIP_LDS
-        walk(lo, hi - lo, lo, hi - lo, std::true_type{});                        // inside: from LDS
-#endif
+        // Outside the window: memory gathers.  Those of the first UP such vectors are only
+        // issued here; the LDS walk below runs while they are in flight, then they are added.
+        const int n_out = (lo - head) + (tail - hi);
+        float gb[UP][REP][VEC];
+#pragma unroll
+        for (int u = 0; u < UP; ++u) {
+            const int cu = bcast_any<LPR, true>(cg0, u);
+#pragma unroll
+            for (int r = 0; r < REP; ++r) {
+                const float *src = (u < n_out && kv[r]) ? B + (long)cu * K + kbase + kl[r] : g_zero_row + kl[r];
+                load_vec<VEC>(src, gb[u][r]);
+            }
+        }
+        // the next item's first chunks: its ranges have arrived by now, and the LDS walk
+        // below covers the latency of these loads
+        int cg0_next, cl0_next;
+        float avg0_next[V], avl0_next[V];
+        load_entry(head_next, lo_next - head_next, hi_next, (lo_next - head_next) + (tail_next - hi_next), 0,
+                   cg0_next, avg0_next);
+        load_entry(lo_next, hi_next - lo_next, lo_next, hi_next - lo_next, 0, cl0_next, avl0_next);
+        // inside the window: LDS reads
+        walk(lo, hi - lo, lo, hi - lo, 0, cl0, avl0, std::true_type{});
+        // the gathers issued above
+#pragma unroll
+        for (int u = 0; u < UP; ++u)
+#pragma unroll
+            for (int r = 0; r < REP; ++r)
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        if constexpr (LPR == 16)
+                            fmac_bcast16_const(acc[v][r][e], avg0[v], gb[u][r][e], u);
+                        else
+                            acc[v][r][e] = fmaf(bcast<LPR>(avg0[v], u), gb[u][r][e], acc[v][r][e]);
+                    }
+        // the rare item with more out-of-window vectors than that: the rest, one step at a time
+        if (n_out > UP) {
+            int cg;
+            float avg[V];
+            load_entry(head, lo - head, hi, n_out, UP, cg, avg);
+            walk(head, lo - head, hi, n_out, UP, cg, avg, std::false_type{});
+        }
 
 #pragma unroll
         for (int v = 0; v < V; ++v) {
@@ -776,6 +835,13 @@ __global__ void __launch_bounds__(1024) spmm_window_kernel(SpmmArgs a)
         tail = tail_next;
         lo = lo_next;
         hi = hi_next;
+        cg0 = cg0_next;
+        cl0 = cl0_next;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            avg0[v] = avg0_next[v];
+            avl0[v] = avl0_next[v];
+        }
     }
 }
 

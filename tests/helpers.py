@@ -57,3 +57,9 @@ def column_ordered_schedule(rowptr, colidx, trow, P):
     order = np.concatenate(order) if M else np.zeros(0, np.int64)
     sched = np.stack([rowptr[order], length[order], trow[order], slot[order]], axis=1).astype(np.int32)
     return sched, np.asarray(xb, np.int32)
+
+
+def near_diagonal_share(rowptr, colidx, width=512):
+    """Share of the nonzeros with |column - row| < width (the library's own 17th feature)."""
+    rows = np.repeat(np.arange(rowptr.shape[0] - 1, dtype=np.int64), np.diff(rowptr.astype(np.int64)))
+    return float(np.mean(np.abs(colidx.astype(np.int64) - rows) < width)) if colidx.size else 0.0

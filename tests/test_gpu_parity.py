@@ -12,7 +12,7 @@ import oracle
 import paper_2605_15695_amd as pc
 from oracle import pcsr_format as pf
 import synth
-from tests.helpers import column_ordered_schedule, random_csr
+from tests.helpers import column_ordered_schedule, near_diagonal_share, random_csr
 
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
@@ -808,8 +808,12 @@ def test_gpu_side_features_match_reference(name, omega):
     f = pc.pcsr_features(g.n_rows, g.n_cols, torch.from_numpy(g.rowptr).cuda(),
                          torch.from_numpy(g.colidx).cuda(), omega)
     r = pf.features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega)
-    assert np.allclose(f, r, rtol=1e-11, atol=0), (f, r)
+    assert np.allclose(f[:16], r, rtol=1e-11, atol=0), (f, r)
+    assert f[16] == pytest.approx(near_diagonal_share(g.rowptr, g.colidx), rel=1e-12)
+    assert np.array_equal(f, pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega)) or \
+        np.allclose(f, pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega), rtol=1e-11)
     # degenerate shapes
     z = pc.pcsr_features(3, 5, torch.zeros(4, dtype=torch.int32, device="cuda"),
                          torch.zeros(0, dtype=torch.int32, device="cuda"), omega)
-    assert np.array_equal(z, pf.features(3, 5, np.zeros(4, np.int32), np.zeros(0, np.int32), omega))
+    assert np.array_equal(z[:16], pf.features(3, 5, np.zeros(4, np.int32), np.zeros(0, np.int32), omega))
+    assert z[16] == 0.0

@@ -11,7 +11,7 @@ import paper_2605_15695_amd as pc
 from oracle import pcsr_format as pf
 import synth
 from paper_2605_15695_amd import binding
-from tests.helpers import column_ordered_schedule, random_csr
+from tests.helpers import column_ordered_schedule, near_diagonal_share, random_csr
 
 ROOT = pathlib.Path(__file__).resolve().parent.parent
 HOST = pc.PCSR_FLAG_HOST_ONLY
@@ -79,8 +79,20 @@ def test_features_match_reference(name, omega):
     g = synth.workload(name, "small")
     f = pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega)
     r = pf.features(g.n_rows, g.n_cols, g.rowptr, g.colidx, omega)
-    assert np.allclose(f, r, rtol=1e-12, atol=0)
+    assert np.allclose(f[:16], r, rtol=1e-12, atol=0)          # Table 3
     assert f[14] == 0.0 and 0.0 <= f[15] <= 0.5 and f[9] >= 1.0 and f[10] >= 1.0
+    assert f[16] == pytest.approx(near_diagonal_share(g.rowptr, g.colidx), rel=1e-12)   # the library's own
+
+
+def test_near_diagonal_feature_closed_forms():
+    n = 3000
+    eye_rp, eye_ci = np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32)
+    assert pc.pcsr_features(n, n, eye_rp, eye_ci)[16] == 1.0
+    far = ((np.arange(n) + 512) % n).astype(np.int32)            # every nonzero exactly 512 (or more) away
+    assert pc.pcsr_features(n, n, eye_rp, far)[16] == 0.0
+    near = ((np.arange(n) + 511) % n).astype(np.int32)
+    assert pc.pcsr_features(n, n, eye_rp, near)[16] == pytest.approx((n - 511) / n)
+    assert pc.pcsr_features(3, 5, np.zeros(4, np.int32), np.zeros(0, np.int32))[16] == 0.0
 
 
 def test_gap_export_matches_table2():
@@ -285,3 +297,27 @@ def test_reorder_by_degree():
     with pytest.raises(pc.PcsrError):
         pc.pcsr_reorder_by_degree(2, np.array([0, 1, 2], np.int32), np.array([0, 5], np.int32))
     assert pc.pcsr_reorder_by_degree(0, np.zeros(1, np.int32), np.zeros(0, np.int32)).size == 0
+
+
+def test_selector_proposes_the_window_only_where_the_build_keeps_it():
+    g = synth.workload("sbm", "small")                       # 24 communities of 500 consecutive ids
+    sel = pc.pcsr_select(pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx), 128)
+    assert sel.col_window == 512 and sel.S == 0 and sel.flags & pc.PCSR_FLAG_WINDOW_IF_USEFUL
+    sel.flags |= HOST
+    h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, sel)
+    st = pc.pcsr_window_stats(h)
+    assert st["col_window"] == 512 and st["hit_fraction"] > 0.85 and st["items_per_block"] == 500
+    assert pc.pcsr_query_launch(h, 128)["lds_bytes"] > 0
+    h.close()
+    # the same request on the shuffled graph: the build finds no blocks and drops the window
+    gs = synth.workload("sbm_shuffled", "small")
+    assert pc.pcsr_select(pc.pcsr_features(gs.n_rows, gs.n_cols, gs.rowptr, gs.colidx), 128).col_window == 0
+    h = pc.pcsr_build(gs.n_rows, gs.n_cols, gs.rowptr, gs.colidx, gs.vals, sel)
+    assert pc.pcsr_window_stats(h)["col_window"] == 0
+    q = pc.pcsr_query_launch(h, 128)
+    assert q["lds_bytes"] == 0 and q["waves_per_wg"] <= 8
+    h.close()
+    # without the flag the window blocks are kept whatever they look like
+    h = pc.pcsr_build(gs.n_rows, gs.n_cols, gs.rowptr, gs.colidx, gs.vals, pc.make_params(col_window=512, flags=HOST))
+    assert pc.pcsr_window_stats(h)["col_window"] == 512
+    h.close()
