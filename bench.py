@@ -23,9 +23,21 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per SpMM launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
 # each scaled by what the counter reads for a plain copy kernel of known size); the
-# summaries with the commands are under profiles/.  Keyed by workload, K and the kernel
-# instance that was profiled: a run that launches another instance reports null.
+# summaries with the commands are under profiles/.  Keyed by workload, K, the kernel instance
+# that was profiled, the item size SG and the item schedule: a run that launches another
+# instance, or the same instance over another PCSR layout, reports null.
 PROFILED_TRAFFIC = {
+    ("poisson-full", 32, "spmm_kernel<1, false, 8, 4, 1>", 0, "index"): 3509284,
+    ("road-full", 128, "spmm_kernel<2, false, 32, 4, 1>", 0, "index"): 2121477869,
+    ("rmat20-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 64, "column"): 2179788032,
+    ("sbm-full", 256, "spmm_window_kernel<1, 16, 4, 1>", 0, "index"): 2229595538,
+    ("sbm_shuffled-full", 256, "spmm_kernel<1, false, 64, 4, 1>", 0, "index"): 12449157046,
+    ("rmat22-full", 16, "spmm_kernel<1, true, 4, 4, 1>", 64, "column"): 11868661248,
+    ("rmat22-full", 32, "spmm_kernel<1, true, 8, 4, 1>", 64, "column"): 10371347986,
+    ("rmat22-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 64, "column"): 19287959936,
+    ("rmat22-full", 128, "spmm_kernel<1, true, 16, 4, 1>", 64, "column"): 38868242212,
+    ("rmat22-full", 256, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 74994487588,
+    ("rmat22-full", 512, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 155900882651,
 }
 
 
@@ -146,6 +158,8 @@ def main() -> int:
     build_ms = (time.time() - t0) * 1e3
     launch = pc.pcsr_query_launch(h, K)
     instance = kernel_instance(V, S, launch)
+    schedule = "column" if (int(params.flags) & pc.PCSR_FLAG_COLUMN_ORDER) and S else "index"
+    workload_name = f"{args.workload}-{args.size}" + (f"+reorder({args.reorder})" if args.reorder else "")
     pc.pcsr_reserve_workspace(h, K)
 
     Bd = torch.from_numpy(B).cuda()
@@ -196,13 +210,13 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}-{args.size}" + (f"+reorder({args.reorder})" if args.reorder else ""),
-                   "graph": g.name, "n": g.n_rows,
-                   "nnz": g.nnz, "K": K, "V": V, "S": S, "SG": int(params.SG), **launch, "kernel": instance,
+        "config": {"workload": workload_name, "graph": g.name, "n": g.n_rows,
+                   "nnz": g.nnz, "K": K, "V": V, "S": S, "SG": int(params.SG), "schedule": schedule,
+                   **launch, "kernel": instance,
                    "workspace_bytes": pc.pcsr_workspace_bytes(h, K)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": PROFILED_TRAFFIC.get((f"{args.workload}-{args.size}", K, instance)),
+                     "traffic": PROFILED_TRAFFIC.get((workload_name, K, instance, int(params.SG), schedule)),
                      "kernel_ms_mean": kern_ms, "kernel_ms_median": statistics.median(per_launch_ms),
                      "kernel_ms_min": min(per_launch_ms), "algorithmic_bytes": bytes_min},
         "setup": {"generate_s": gen_s, "features_select_ms": feat_ms, "pcsr_build_ms": build_ms,

@@ -687,8 +687,19 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // the long rows, sorted by first column, make the wavefronts of an XCD gather the same B
     // rows at about the same time (R-MAT scale 22: 1.6-2x over the best index-order tuple at
     // every width from 16 to 512; neutral on small or uniform inputs).
-    p.S = (cv > 1.5 && d_max > 256.0) ? 1 : 0;
-    p.SG = p.S ? (K >= 256 ? 32 : 64) : 0;
+    const bool skewed = cv > 1.5 && d_max > 256.0;
+    const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
+    // Rows that gather from a neighbourhood of their own index are served from LDS instead
+    // (see the column window below).
+    const bool windowed = !skewed && f[16] >= 0.6 && d_hat >= 40.0 && vec == 4;
+    // Uniformly long rows with scattered columns (mean length 40 or more, so that the
+    // average row gives two or more items of 32): the same column-ordered schedule turns
+    // the split into a column partition of A, each XCD gathering from its own range of B
+    // rows (uniform random columns, 96 per row, K = 128: 1.5x; 48 per row, K = 256: 1.13x;
+    // at 32 per row the second items are too short and it loses 15 %).
+    const bool long_uniform = !skewed && !windowed && d_hat >= 40.0;
+    p.S = (skewed || long_uniform) ? 1 : 0;
+    p.SG = skewed ? (K >= 256 ? 32 : 64) : (long_uniform ? 32 : 0);
     p.omega = 64;
     if (p.S) p.flags |= PCSR_FLAG_COLUMN_ORDER;
     // Vector size 2 (Section 3.1) when adjacent rows share columns, and for short rows, where
@@ -700,13 +711,12 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
 
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.
-    const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
     // Balanced power-law inputs do best without repeats and, once B outgrows the 256 MB
     // memory-side cache, with 64-column slices (four items per wavefront; grid.y covers
     // wider rows), which shrinks the bytes a cached B row occupies; a smaller B is gathered
     // in 128-column slices.
     const double b_bytes = f[0] * (double)K * 4.0;
-    const int lpr_cap = p.S ? (b_bytes > 192.0 * 1048576.0 ? 16 : 32) : 64;
+    const int lpr_cap = p.S ? ((long_uniform || b_bytes > 192.0 * 1048576.0) ? 16 : 32) : 64;
     int lpr = 4;
     while (lpr * vec < K && lpr < lpr_cap) lpr <<= 1;
     int rep = 1;
@@ -729,7 +739,7 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // (K = 32) to 1.4x (K = 512) faster from LDS than from L2; cliques of 25 or blocks of 50
     // nodes do not repay the staging.  The build drops the window again if the blocks it
     // finds are poor.
-    if (!p.S && f[16] >= 0.6 && d_hat >= 40.0 && vec == 4) {
+    if (windowed) {
         p.V = 1;
         p.col_window = 512;
         p.flags |= PCSR_FLAG_WINDOW_IF_USEFUL;

@@ -308,62 +308,83 @@ int choose_windows(HostPcsr *hp, int32_t win_cols)
     if (win_cols <= 0) return PCSR_OK;
     try {
         const int64_t M = h.M;
-        constexpr int64_t kProbe = 32; // items whose columns propose a block's window
-        // first column of the densest window of win_cols columns over items [i0, i1), and the
-        // vectors that fall inside it
-        std::vector<int32_t> cols;
-        auto densest = [&](int64_t i0, int64_t i1, int64_t *hits) -> int64_t {
-            const int64_t s = h.rowptr[i0], e = h.rowptr[i1];
-            *hits = 0;
-            if (e <= s) return -1;
-            cols.assign(h.colidx.begin() + s, h.colidx.begin() + e);
-            std::sort(cols.begin(), cols.end());
-            int64_t best = 0, best_lo = 0, l = 0;
-            for (int64_t r = 0; r < (int64_t)cols.size(); ++r) {
-                while (cols[r] - cols[l] >= win_cols) ++l;
-                if (r - l + 1 > best) {
-                    best = r - l + 1;
-                    best_lo = l;
+        constexpr int64_t kProbe = 32;     // items whose columns propose a block's window
+        constexpr int64_t kSegment = 8192; // blocks never cross a multiple of this many items, so
+                                           // segments can be cut in parallel with the same result
+        struct Cut {
+            std::vector<int32_t> ptr_end, start; // per block: one past its last item, window start
+            int64_t hits = 0;
+        };
+        const int64_t n_seg = ceildiv(M, kSegment);
+        std::vector<Cut> cuts(n_seg);
+        parallel_for(n_seg, 1, [&](int64_t s0, int64_t s1) {
+            std::vector<int32_t> cols;
+            // first column of the densest window of win_cols columns over items [i0, i1), and
+            // the vectors that fall inside it
+            auto densest = [&](int64_t i0, int64_t i1, int64_t *hits) -> int64_t {
+                const int64_t s = h.rowptr[i0], e = h.rowptr[i1];
+                *hits = 0;
+                if (e <= s) return -1;
+                cols.assign(h.colidx.begin() + s, h.colidx.begin() + e);
+                std::sort(cols.begin(), cols.end());
+                int64_t best = 0, best_lo = 0, l = 0;
+                for (int64_t r = 0; r < (int64_t)cols.size(); ++r) {
+                    while (cols[r] - cols[l] >= win_cols) ++l;
+                    if (r - l + 1 > best) {
+                        best = r - l + 1;
+                        best_lo = l;
+                    }
+                }
+                int64_t c0 = cols[best_lo];
+                c0 = std::min<int64_t>(c0, std::max<int64_t>(0, h.n_cols - win_cols));
+                int64_t cnt = 0;
+                for (int32_t c : cols) cnt += (c >= c0 && c < c0 + win_cols);
+                *hits = cnt;
+                return c0;
+            };
+            for (int64_t sg = s0; sg < s1; ++sg) {
+                Cut &cut = cuts[sg];
+                const int64_t seg_end = std::min<int64_t>(M, (sg + 1) * kSegment);
+                // A block grows item by item while the items keep gathering from the window its
+                // first kProbe items proposed (at least half of an item's vectors inside), up
+                // to win_cols items; where the matrix has no such structure blocks are kProbe
+                // items long.
+                for (int64_t i = sg * kSegment; i < seg_end;) {
+                    const int64_t probe_end = std::min<int64_t>(seg_end, i + kProbe);
+                    int64_t hits = 0;
+                    const int64_t c_probe = densest(i, probe_end, &hits);
+                    int64_t j = probe_end;
+                    if (c_probe >= 0) {
+                        for (; j < seg_end && j - i < win_cols; ++j) {
+                            const int64_t s = h.rowptr[j], e = h.rowptr[j + 1];
+                            if (e == s) continue;
+                            const int64_t in =
+                                std::lower_bound(h.colidx.begin() + s, h.colidx.begin() + e,
+                                                 (int32_t)std::min<int64_t>(c_probe + win_cols, INT32_MAX)) -
+                                std::lower_bound(h.colidx.begin() + s, h.colidx.begin() + e, (int32_t)c_probe);
+                            if (2 * in < e - s) break;
+                        }
+                    }
+                    // the block's own window; staging costs win_cols row reads, worth it from
+                    // two uses per staged row
+                    const int64_t c0 = densest(i, j, &hits);
+                    if (c0 >= 0 && hits >= 2 * (int64_t)win_cols) {
+                        cut.start.push_back((int32_t)c0);
+                        cut.hits += hits;
+                    } else {
+                        cut.start.push_back(-1);
+                    }
+                    cut.ptr_end.push_back((int32_t)j);
+                    i = j;
                 }
             }
-            int64_t c0 = cols[best_lo];
-            c0 = std::min<int64_t>(c0, std::max<int64_t>(0, h.n_cols - win_cols));
-            int64_t cnt = 0;
-            for (int32_t c : cols) cnt += (c >= c0 && c < c0 + win_cols);
-            *hits = cnt;
-            return c0;
-        };
-        // A block grows item by item while the items keep gathering from the window its first
-        // kProbe items proposed (at least half of an item's vectors inside), up to win_cols
-        // items; where the matrix has no such structure blocks are kProbe items long.
+        });
         int64_t total_hits = 0;
         h.win_ptr.push_back(0);
-        for (int64_t i = 0; i < M;) {
-            const int64_t probe_end = std::min<int64_t>(M, i + kProbe);
-            int64_t hits = 0;
-            const int64_t c_probe = densest(i, probe_end, &hits);
-            int64_t j = probe_end;
-            if (c_probe >= 0) {
-                for (; j < M && j - i < win_cols; ++j) {
-                    const int64_t s = h.rowptr[j], e = h.rowptr[j + 1];
-                    if (e == s) continue;
-                    const int64_t in = std::lower_bound(h.colidx.begin() + s, h.colidx.begin() + e,
-                                                        (int32_t)std::min<int64_t>(c_probe + win_cols, INT32_MAX)) -
-                                       std::lower_bound(h.colidx.begin() + s, h.colidx.begin() + e, (int32_t)c_probe);
-                    if (2 * in < e - s) break;
-                }
-            }
-            // the block's own window; staging costs win_cols row reads, worth it from two
-            // uses per staged row
-            const int64_t c0 = densest(i, j, &hits);
-            if (c0 >= 0 && hits >= 2 * (int64_t)win_cols) {
-                h.win_start.push_back((int32_t)c0);
-                total_hits += hits;
-            } else {
-                h.win_start.push_back(-1);
-            }
-            h.win_ptr.push_back((int32_t)j);
-            i = j;
+        for (const Cut &cut : cuts) {
+            h.win_ptr.insert(h.win_ptr.end(), cut.ptr_end.begin(), cut.ptr_end.end());
+            h.win_start.insert(h.win_start.end(), cut.start.begin(), cut.start.end());
+            total_hits += cut.hits;
         }
         h.win_hit = h.nnz_v ? double(total_hits) / double(h.nnz_v) : 0.0;
         // the run of every item that lies inside its block's window

@@ -30,7 +30,7 @@ def records_table(recs) -> None:
                 k = name(r)
                 if k not in by or r["ms_median"] < by[k]["ms_median"]:
                     by[k] = r
-            rows = sorted(by.items(), key=lambda kv: kv[1]["ms_median"])[:10]
+            rows = sorted(by.items(), key=lambda kv: kv[1]["ms_median"])[:6]
             print(f"| {title} | best ms | % of input's best | reached with |")
             print("|---|---|---|---|")
             for k, r in rows:

@@ -15,6 +15,8 @@ can be fed identical inputs.  Everything returned is a numpy array:
 from __future__ import annotations
 
 import dataclasses
+import os
+import pathlib
 
 import numpy as np
 
@@ -234,6 +236,25 @@ def sbm(n: int = 250_000, n_blocks: int = 500, mean_deg: float = 50.0, p_intra: 
 # name -> (graph factory, B distribution, default K list).  "full" sizes follow the
 # benchmark configurations; "small" sizes are what the CPU oracle finishes in seconds.
 def workload(name: str, size: str = "full") -> Graph:
+    """The named workload.  With SYNTH_CACHE_DIR set, generated graphs are kept there as
+    .npz files and read back on later calls (the scale-22 R-MAT takes about half a minute to
+    draw); the arrays are the same either way."""
+    cache = os.environ.get("SYNTH_CACHE_DIR")
+    if not cache:
+        return _generate(name, size)
+    path = pathlib.Path(cache) / f"{name}-{size}.npz"
+    if path.exists():
+        z = np.load(path, allow_pickle=False)
+        return Graph(str(z["name"]), int(z["n_rows"]), int(z["n_cols"]), z["rowptr"], z["colidx"], z["vals"])
+    g = _generate(name, size)
+    path.parent.mkdir(parents=True, exist_ok=True)
+    tmp = path.with_suffix(".tmp.npz")
+    np.savez(tmp, name=g.name, n_rows=g.n_rows, n_cols=g.n_cols, rowptr=g.rowptr, colidx=g.colidx, vals=g.vals)
+    tmp.replace(path)
+    return g
+
+
+def _generate(name: str, size: str) -> Graph:
     full = size == "full"
     if name == "poisson":
         return poisson_uniform(4096 if full else 1024)
@@ -272,6 +293,22 @@ EXTRA = {
     "x_cliques": lambda: cliques(300_000, 24.0, 0.1, BASE_SEED + 21),
     "x_cliques_noisy": lambda: cliques(300_000, 24.0, 0.5, BASE_SEED + 22),
 }
+
+# A second such set, drawn after the rule had been revised with the first set in view, so
+# that the score on it says something about inputs the rule has never been compared with.
+EXTRA2 = {
+    "y_poisson_d64": lambda: poisson_like(150_000, 64.0, BASE_SEED + 31),
+    "y_poisson_d160": lambda: poisson_like(30_000, 160.0, BASE_SEED + 32),
+    "y_poisson_d16": lambda: poisson_like(500_000, 16.0, BASE_SEED + 33),
+    "y_sbm_shuffled_d72": lambda: sbm(90_000, 300, mean_deg=72.0, shuffled=True, seed=BASE_SEED + 34),
+    "y_sbm_d72": lambda: sbm(90_000, 300, mean_deg=72.0, seed=BASE_SEED + 34),
+    "y_sbm_d44_leaky": lambda: sbm(160_000, 400, mean_deg=44.0, p_intra=0.75, seed=BASE_SEED + 35),
+    "y_rmat16_ef32": lambda: rmat(16, 32, permute=True, symmetric=True, seed=BASE_SEED + 36),
+    "y_rmat21_ef4": lambda: rmat(21, 4, permute=False, symmetric=False, seed=BASE_SEED + 37),
+    "y_road_wide": lambda: road_grid(3000, 300, mean_draw=3.0, seed=BASE_SEED + 38),
+    "y_cliques_big": lambda: cliques(200_000, 48.0, 0.2, BASE_SEED + 39),
+}
+EXTRA.update(EXTRA2)
 
 
 def cliques(n: int, mean_size: float, noise: float, seed: int) -> Graph:

@@ -306,7 +306,7 @@ def test_selector_proposes_the_window_only_where_the_build_keeps_it():
     sel.flags |= HOST
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, sel)
     st = pc.pcsr_window_stats(h)
-    assert st["col_window"] == 512 and st["hit_fraction"] > 0.85 and st["items_per_block"] == 500
+    assert st["col_window"] == 512 and st["hit_fraction"] > 0.85 and 400 <= st["items_per_block"] <= 500
     assert pc.pcsr_query_launch(h, 128)["lds_bytes"] > 0
     h.close()
     # the same request on the shuffled graph: the build finds no blocks and drops the window
