@@ -138,8 +138,10 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
  * Write-back (Algorithm 2, last block).  S = 0: one plain store per row of C.  S = 1: a
  * panel that the workload split left whole is stored the same way; the items of a panel
  * that was split each leave their partial rows in a workspace owned by the handle
- * (V*K floats per such item) and a second kernel adds them in item order and stores the
- * row once.  No atomics, no clearing of C: for a given handle, kernel parameters and K the
+ * (V*K floats per such item) and a second pass adds them and stores the row once: in
+ * item order for a panel of up to 64 items; for a longer panel 16 threads per element
+ * each add every 16th item in order and the 16 partial sums are then added in order (the
+ * order depends on the item numbers alone, not on the launch or the schedule).  No atomics, no clearing of C: for a given handle, kernel parameters and K the
  * result is the same bits on every run, for S = 0 and S = 1 alike.  With
  * PCSR_FLAG_ATOMIC_SPLIT the split panels are cleared and accumulated with fp32 atomics
  * instead (no workspace; summation order, hence the last bits, may vary between runs).

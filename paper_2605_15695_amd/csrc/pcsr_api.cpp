@@ -54,6 +54,8 @@ struct pcsr_handle_s {
     int32_t *d_item_slot = nullptr;   // per item: workspace slot, -1 for a sole item (S only)
     int32_t *d_sched = nullptr;       // column-ordered schedule: 4 int32 per launch position
     int32_t *d_split_slot = nullptr;  // their first workspace slots (n_split + 1 entries)
+    int32_t *d_long = nullptr;        // positions in d_split of panels with more than kLongPanelSlots items
+    int64_t n_long = 0;
     int32_t *d_win = nullptr;     // window start per item block
     int32_t *d_win_ptr = nullptr; // item range per item block
     int32_t *d_win_lo = nullptr;  // per item: run of vectors inside the block's window
@@ -80,13 +82,14 @@ void release_device(pcsr_handle_t h)
     if (h->d_item_slot) (void)hipFree(h->d_item_slot);
     if (h->d_sched) (void)hipFree(h->d_sched);
     if (h->d_split_slot) (void)hipFree(h->d_split_slot);
+    if (h->d_long) (void)hipFree(h->d_long);
     if (h->d_win) (void)hipFree(h->d_win);
     if (h->d_win_ptr) (void)hipFree(h->d_win_ptr);
     if (h->d_win_lo) (void)hipFree(h->d_win_lo);
     if (h->d_win_hi) (void)hipFree(h->d_win_hi);
     if (h->d_ws) (void)hipFree(h->d_ws);
     h->d_rowptr = h->d_colidx = h->d_trow = h->d_split = h->d_win = nullptr;
-    h->d_item_slot = h->d_sched = h->d_split_slot = h->d_win_ptr = nullptr;
+    h->d_item_slot = h->d_sched = h->d_split_slot = h->d_long = h->d_win_ptr = nullptr;
     h->d_win_lo = h->d_win_hi = nullptr;
     h->d_val = h->d_ws = nullptr;
     h->ws_bytes = 0;
@@ -106,6 +109,20 @@ template <class T> int upload(const std::vector<T> &src, T **dst)
     if (!src.empty() && !hip_ok(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice)))
         return PCSR_E_HIP;
     return PCSR_OK;
+}
+
+// Lists the split panels (by position in the split tables) with more than
+// pcsr::kLongPanelSlots items and puts the list in device memory: the second pass of the
+// balanced write-back gives those panels a workgroup each.  split_slot: n_split + 1 entries
+// in host memory.
+static int upload_long_panels(pcsr_handle_s *h, const int32_t *split_slot)
+{
+    std::vector<int32_t> list;
+    for (int64_t q = 0; q < h->n_split; ++q)
+        if (split_slot[q + 1] - split_slot[q] > pcsr::kLongPanelSlots) list.push_back((int32_t)q);
+    h->n_long = (int64_t)list.size();
+    if (list.empty()) return PCSR_OK;
+    return upload(list, &h->d_long);
 }
 
 // Launch shape for width K under the handle's kernel parameters ("0 = auto" resolved).
@@ -292,6 +309,23 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             delete h;
             return PCSR_E_HIP;
         }
+        if (h->n_split > 0) {
+            int rc2 = PCSR_E_OOM;
+            try {
+                std::vector<int32_t> slots((size_t)h->n_split + 1);
+                rc2 = hip_ok(hipMemcpy(slots.data(), h->d_split_slot, slots.size() * sizeof(int32_t),
+                                       hipMemcpyDeviceToHost))
+                          ? upload_long_panels(h, slots.data())
+                          : PCSR_E_HIP;
+            } catch (const std::bad_alloc &) {
+                rc2 = PCSR_E_OOM;
+            }
+            if (rc2 != PCSR_OK) {
+                release_device(h);
+                delete h;
+                return rc2;
+            }
+        }
         *out = h;
         return PCSR_OK;
     }
@@ -378,6 +412,7 @@ int pcsr_build(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowpt
             if (rc == PCSR_OK && h->host.S) rc = upload(h->host.item_slot, &h->d_item_slot);
             if (rc == PCSR_OK && !h->host.sched.empty()) rc = upload(h->host.sched, &h->d_sched);
             if (rc == PCSR_OK && h->n_split) rc = upload(h->host.split_slot, &h->d_split_slot);
+            if (rc == PCSR_OK && h->n_split) rc = upload_long_panels(h, h->host.split_slot.data());
             if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_start, &h->d_win);
             if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_ptr, &h->d_win_ptr);
             if (rc == PCSR_OK && h->host.win_cols) rc = upload(h->host.win_lo, &h->d_win_lo);
@@ -477,7 +512,7 @@ static int spmm_enqueue(pcsr_handle_t h, const float *B, float *C, int32_t K, co
     a.n_cols = (int32_t)h->host.n_cols;
     if (!hip_ok(pcsr::launch_spmm(h->host.V, h->host.S, ls, a, s))) return PCSR_E_HIP;
     if (two_pass) {
-        if (!hip_ok(pcsr::launch_reduce_split(h->d_split, h->d_split_slot, h->n_split, h->host.V, ws, C,
+        if (!hip_ok(pcsr::launch_reduce_split(h->d_split, h->d_split_slot, h->n_split, h->d_long, h->n_long, h->host.V, ws, C,
                                               (int32_t)h->host.n_rows, K, s)))
             return PCSR_E_HIP;
     }
@@ -683,31 +718,50 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     const double d_hat = f[5], d_max = f[6], cv = f[7], pr2 = f[15];
 
     // Balancing (Section 3.2) pays when a few rows dwarf the average one.  On MI355X the
-    // recorded sweeps then prefer short items (64 vectors, 32 from K = 256) run in column order: the items of
+    // recorded sweeps then prefer short items (32 vectors with slices of up to 64 columns, 64
+    // vectors with 128-column slices) run in column order: the items of
     // the long rows, sorted by first column, make the wavefronts of an XCD gather the same B
     // rows at about the same time (R-MAT scale 22: 1.6-2x over the best index-order tuple at
     // every width from 16 to 512; neutral on small or uniform inputs).
     const bool skewed = cv > 1.5 && d_max > 256.0;
     const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
     // Rows that gather from a neighbourhood of their own index are served from LDS instead
-    // (see the column window below).
-    const bool windowed = !skewed && f[16] >= 0.6 && d_hat >= 40.0 && vec == 4;
-    // Uniformly long rows with scattered columns (mean length 40 or more, so that the
-    // average row gives two or more items of 32): the same column-ordered schedule turns
-    // the split into a column partition of A, each XCD gathering from its own range of B
-    // rows (uniform random columns, 96 per row, K = 128: 1.5x; 48 per row, K = 256: 1.13x;
-    // at 32 per row the second items are too short and it loses 15 %).
-    const bool long_uniform = !skewed && !windowed && d_hat >= 40.0;
-    p.S = (skewed || long_uniform) ? 1 : 0;
-    p.SG = skewed ? (K >= 256 ? 32 : 64) : (long_uniform ? 32 : 0);
+    // (see the column window below), from K = 64 (at 32 it ties with the plain kernel) and if
+    // the product is large enough to give every compute unit a few window blocks: a block
+    // occupies a whole compute unit, and with too few rounds of blocks the last one leaves
+    // most of the chip idle (90,000 rows in communities of 300: 0.55x of the plain kernel
+    // at K = 32, 0.81x at K = 128; 200,000 rows at K = 64: 1.1x).
+    const double n = f[0];
+    // Rows that share most columns with their neighbour (padding below 30 %) do better
+    // paired, V = 2, than from LDS (cliques of 48, K = 128: 0.98 against 0.82 of the best).
+    const bool windowed = !skewed && f[16] >= 0.6 && d_hat >= 40.0 && vec == 4 && pr2 >= 0.3 && K >= 64 &&
+                          n * (double)((K + 63) / 64) >= 200000.0;
+    // Uniformly long rows with scattered columns (mean length 40 or more, no more nonzeros
+    // near the diagonal than four times what uniform columns would put there).  From
+    // K = 64 the same column-ordered schedule, with items of 32, turns the split into a
+    // column partition of A, each XCD gathering from its own range of B rows (uniform
+    // random columns, 96 per row, K = 128: 1.5x; 48 per row, K = 256: 1.13x; at 32 per
+    // row the second items are too short and it loses 15 %).  Narrower B rows are cached
+    // well enough as they are; there pairing rows (V = 2) wins, by doubling the gathers a
+    // lane group has in flight.  Rows with local columns lose up to half their speed under
+    // the column order (it gives up the reuse between neighbouring rows).
+    const bool scattered = f[16] < 4.0 * 1025.0 / (n > 1.0 ? n : 1.0);
+    const bool long_uniform = !skewed && !windowed && d_hat >= 40.0 && scattered;
+    const bool long_uniform_wide = long_uniform && K >= 64;
+    p.S = (skewed || long_uniform_wide) ? 1 : 0;
+    p.SG = p.S ? 32 : 0; // power-law inputs: raised to 64 below for 128-column slices
     p.omega = 64;
     if (p.S) p.flags |= PCSR_FLAG_COLUMN_ORDER;
     // Vector size 2 (Section 3.1) when adjacent rows share columns, and for short rows, where
     // pairing rows doubles the gathers a lane group keeps in flight.  The paper's A6000 data
     // puts the break-even near 30 % padding; on MI355X clique-like inputs win at 11 %
     // padding (1.23x at K=128) and lose at 27 %, because adjacent rows of one wavefront
-    // already share their B lines in L1.  Balanced inputs: V = 2 ties or loses in the sweeps.
-    p.V = (!p.S && (d_hat < 6.0 || (d_hat < 12.0 && pr2 < 0.45) || pr2 < 0.20)) ? 2 : 1;
+    // already share their B lines in L1.  Power-law inputs: V = 2 ties or loses in the sweeps.
+    // Long scattered rows at K below 64 (above): paired as well, unless the matrix is so small
+    // that halving the number of work items leaves wavefront slots empty (30,000 rows of
+    // 160, K = 32: V = 2 runs at 0.55 of V = 1).
+    const bool pair_long = long_uniform && n * (double)(K < 32 ? 4 : 8) / 128.0 >= 3500.0;
+    p.V = (!p.S && (d_hat < 6.0 || (d_hat < 12.0 && pr2 < 0.45) || pr2 < 0.20 || pair_long)) ? 2 : 1;
 
     // Launch shape: the widest vector load that divides K, one lane group spanning the
     // whole row of C when it fits a wavefront, repeats beyond that.
@@ -716,7 +770,7 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // wider rows), which shrinks the bytes a cached B row occupies; a smaller B is gathered
     // in 128-column slices.
     const double b_bytes = f[0] * (double)K * 4.0;
-    const int lpr_cap = p.S ? ((long_uniform || b_bytes > 192.0 * 1048576.0) ? 16 : 32) : 64;
+    const int lpr_cap = p.S ? ((long_uniform_wide || b_bytes > 192.0 * 1048576.0) ? 16 : 32) : 64;
     int lpr = 4;
     while (lpr * vec < K && lpr < lpr_cap) lpr <<= 1;
     int rep = 1;
@@ -728,24 +782,25 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     p.lanes_per_row = lpr;
     p.vec = vec;
     p.rep = rep;
-    // Workgroup size: long uniform rows like full workgroups, short rows and items of
-    // very different lengths smaller ones.
-    p.waves_per_wg = p.S ? 4 : (d_hat >= 16.0 ? 8 : 2);
+    if (skewed && lpr * vec > 64) p.SG = 64;
+    // Workgroup size: four wavefronts, two for short rows and for paired long rows (eight
+    // were 4-7 % slower than four on every unsplit input of the later validation sets).
+    p.waves_per_wg = p.S ? 4 : (d_hat >= 16.0 && !pair_long ? 4 : 2);
     p.items_per_group = 1;
     p.col_window = 0;
     // Column-window blocking: rows that gather from a neighbourhood of their own index (most
     // nonzeros within 512 columns of the diagonal) and are long enough that every staged row
     // of B is used dozens of times.  A 500-node community graph of degree 48 runs 1.1x
-    // (K = 32) to 1.4x (K = 512) faster from LDS than from L2; cliques of 25 or blocks of 50
+    // (K = 64) to 1.4x (K = 512) faster from LDS than from L2; cliques of 25 or blocks of 50
     // nodes do not repay the staging.  The build drops the window again if the blocks it
     // finds are poor.
     if (windowed) {
         p.V = 1;
         p.col_window = 512;
         p.flags |= PCSR_FLAG_WINDOW_IF_USEFUL;
-        p.lanes_per_row = K >= 64 ? 16 : 8; // 64-column slices of the window (136 KiB of LDS)
+        p.lanes_per_row = 16; // 64-column slices of the window (136 KiB of LDS)
         p.rep = 1;
-        p.waves_per_wg = K >= 64 ? 16 : 8;
+        p.waves_per_wg = 16;
     }
     *out = p;
     return PCSR_OK;

@@ -59,11 +59,16 @@ hipError_t launch_zero_panels(const int32_t *panels, int64_t n_panels, int V, fl
                               int32_t n_rows, int32_t K, hipStream_t stream);
 
 // Second pass of the deterministic balanced write-back: for every split panel q and
-// v < V, C[panel*V + v][:] = sum over its items, in item order, of the partial rows the
-// SpMM kernel left in ws.
+// v < V, C[panel*V + v][:] = sum over its items of the partial rows the SpMM kernel left
+// in ws.  Panels with at most kLongPanelSlots items are added in item order by one thread
+// per vector of C; the others (indices into the split tables listed in long_panels,
+// n_long of them) by kLongReduceLanes threads per vector, thread j taking items j,
+// j + kLongReduceLanes, ... in order, the partial sums then added in ascending j.
+constexpr int kLongPanelSlots = 64;
+constexpr int kLongReduceLanes = 16;
 hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split_slot, int64_t n_split,
-                               int V, const float *ws, float *C, int32_t n_rows, int32_t K,
-                               hipStream_t stream);
+                               const int32_t *long_panels, int64_t n_long, int V, const float *ws, float *C,
+                               int32_t n_rows, int32_t K, hipStream_t stream);
 
 // Fixed workspace for callers that cannot allocate: one block of kStaticScratchBytes
 // bytes per GPU, part of the library's device image and held until the process ends.

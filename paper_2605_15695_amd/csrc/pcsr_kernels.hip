@@ -863,12 +863,12 @@ __global__ void __launch_bounds__(256) zero_panels_kernel(const int32_t *__restr
 // One thread per VEC consecutive elements (q, v, k..k+VEC) of the rows of split panels.  The
 // partial rows of panel q sit in consecutive workspace slots in item order and are added in
 // that order, whatever the grid looks like, so the balanced result is the same bits on
-// every run.
+// every run.  Panels with more than `skip_above` slots are left to reduce_long_kernel.
 template <int VEC>
 __global__ void __launch_bounds__(256) reduce_split_kernel(const int32_t *__restrict__ split_panels,
                                                            const int32_t *__restrict__ split_slot,
                                                            long n_split, int V, const float *__restrict__ ws,
-                                                           float *C, int n_rows, int K)
+                                                           float *C, int n_rows, int K, int skip_above)
 {
     const int kv = K / VEC; // vectors per row
     const long total = n_split * V * (long)kv;
@@ -881,6 +881,7 @@ __global__ void __launch_bounds__(256) reduce_split_kernel(const int32_t *__rest
     const long row = (long)split_panels[q] * V + v;
     if (row >= n_rows) return;
     const long s0 = split_slot[q], s1 = split_slot[q + 1];
+    if (s1 - s0 > skip_above) return;
     const long stride = (long)V * K;
     const float *w = ws + (s0 * V + v) * (long)K + k;
     float sum[VEC];
@@ -903,6 +904,62 @@ __global__ void __launch_bounds__(256) reduce_split_kernel(const int32_t *__rest
         for (int e = 0; e < VEC; ++e) sum[e] += t1[e];
     }
     store_vec<VEC>(C + row * K + k, sum);
+}
+
+// Split panels with many partial rows (a hub row of a power-law graph is cut into thousands
+// of items): one workgroup per (panel row, 16 vectors of C), 16 threads per vector.  Thread
+// j of a vector adds slots j, j+16, j+32, ... in ascending order, then the 16 partial sums
+// are added in ascending j.  The order depends on the slot numbers alone, so the result is
+// again the same bits on every run and for every schedule.
+template <int VEC>
+__global__ void __launch_bounds__(256) reduce_long_kernel(const int32_t *__restrict__ long_panels,
+                                                          const int32_t *__restrict__ split_panels,
+                                                          const int32_t *__restrict__ split_slot, int V,
+                                                          const float *__restrict__ ws, float *C, int n_rows,
+                                                          int K)
+{
+    __shared__ float part[kLongReduceLanes][16][VEC];
+    const int c = threadIdx.x % 16, j = threadIdx.x / 16;
+    const long r = blockIdx.x;
+    const long q = long_panels[r / V];
+    const int v = (int)(r % V);
+    const long row = (long)split_panels[q] * V + v;
+    if (row >= n_rows) return; // the whole workgroup leaves: no barrier is skipped by a part of it
+    const int k = ((int)blockIdx.y * 16 + c) * VEC;
+    const bool live = k < K;
+    const long s0 = split_slot[q], s1 = split_slot[q + 1];
+    const long stride = (long)V * K, step = kLongReduceLanes * stride;
+    float sum[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sum[e] = 0.0f;
+    if (live) {
+        long jj = s0 + j;
+        const float *w = ws + (jj * V + v) * (long)K + k;
+        for (; jj + 3 * kLongReduceLanes < s1; jj += 4 * kLongReduceLanes, w += 4 * step) {
+            float t4[4][VEC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) load_vec<VEC>(w + u * step, t4[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) sum[e] += t4[u][e];
+        }
+        for (; jj < s1; jj += kLongReduceLanes, w += step) {
+            float t1[VEC];
+            load_vec<VEC>(w, t1);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sum[e] += t1[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) part[j][c][e] = sum[e];
+    __syncthreads();
+    if (j == 0 && live) {
+        for (int jj = 1; jj < kLongReduceLanes; ++jj)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) sum[e] += part[jj][c][e];
+        store_vec<VEC>(C + row * K + k, sum);
+    }
 }
 
 using KernelFn = void (*)(SpmmArgs);
@@ -1106,8 +1163,8 @@ hipError_t static_scratch(void **ptr)
 }
 
 hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split_slot, int64_t n_split,
-                               int V, const float *ws, float *C, int32_t n_rows, int32_t K,
-                               hipStream_t stream)
+                               const int32_t *long_panels, int64_t n_long, int V, const float *ws, float *C,
+                               int32_t n_rows, int32_t K, hipStream_t stream)
 {
     if (n_split <= 0) return hipSuccess;
     // 16-byte accesses need rows that start on 16-byte boundaries (the workspace always does)
@@ -1116,13 +1173,25 @@ hipError_t launch_reduce_split(const int32_t *split_panels, const int32_t *split
     const int vec = aligned ? 4 : 1;
     const long total = n_split * V * (long)(K / vec);
     const long blocks = (total + 255) / 256;
-    if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+    if (blocks > 0x7fffffffL || n_long * V > 0x7fffffffL) return hipErrorInvalidValue;
+    const int skip_above = n_long > 0 ? kLongPanelSlots : 0x7fffffff;
     if (vec == 4)
         hipLaunchKernelGGL(reduce_split_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, split_panels,
-                           split_slot, (long)n_split, V, ws, C, n_rows, K);
+                           split_slot, (long)n_split, V, ws, C, n_rows, K, skip_above);
     else
         hipLaunchKernelGGL(reduce_split_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, split_panels,
-                           split_slot, (long)n_split, V, ws, C, n_rows, K);
+                           split_slot, (long)n_split, V, ws, C, n_rows, K, skip_above);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n_long <= 0) return e;
+    const int chunks = (K / vec + 15) / 16; // 16 vectors of C per workgroup
+    if (chunks > 65535) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(n_long * V), (unsigned)chunks);
+    if (vec == 4)
+        hipLaunchKernelGGL(reduce_long_kernel<4>, grid, dim3(16 * kLongReduceLanes), 0, stream, long_panels,
+                           split_panels, split_slot, V, ws, C, n_rows, K);
+    else
+        hipLaunchKernelGGL(reduce_long_kernel<1>, grid, dim3(16 * kLongReduceLanes), 0, stream, long_panels,
+                           split_panels, split_slot, V, ws, C, n_rows, K);
     return hipGetLastError();
 }
 

@@ -310,6 +310,32 @@ EXTRA2 = {
 }
 EXTRA.update(EXTRA2)
 
+# A third set, drawn after the second revision of the rule (which had both earlier sets in view).
+EXTRA3 = {
+    "z_poisson_d48": lambda: poisson_like(220_000, 48.0, BASE_SEED + 41),
+    "z_poisson_d120": lambda: poisson_like(50_000, 120.0, BASE_SEED + 42),
+    "z_sbm_shuffled_d56": lambda: sbm(120_000, 240, mean_deg=56.0, shuffled=True, seed=BASE_SEED + 43),
+    "z_sbm_d56_large": lambda: sbm(400_000, 800, mean_deg=56.0, seed=BASE_SEED + 44),
+    "z_sbm_blocks2000": lambda: sbm(100_000, 50, mean_deg=60.0, p_intra=0.8, seed=BASE_SEED + 45),
+    "z_rmat18_ef24": lambda: rmat(18, 24, permute=True, symmetric=False, seed=BASE_SEED + 46),
+    "z_road_sparse": lambda: road_grid(1500, 900, mean_draw=1.6, seed=BASE_SEED + 47),
+    "z_cliques_mid": lambda: cliques(250_000, 32.0, 0.3, BASE_SEED + 48),
+}
+EXTRA.update(EXTRA3)
+
+# A fourth set, drawn after the third revision: the only one the final rule never saw.
+EXTRA4 = {
+    "w_poisson_d80": lambda: poisson_like(100_000, 80.0, BASE_SEED + 51),
+    "w_poisson_d200": lambda: poisson_like(24_000, 200.0, BASE_SEED + 52),
+    "w_sbm_shuffled_d44": lambda: sbm(300_000, 600, mean_deg=44.0, shuffled=True, seed=BASE_SEED + 53),
+    "w_sbm_d64_mid": lambda: sbm(200_000, 500, mean_deg=64.0, seed=BASE_SEED + 54),
+    "w_rmat19_ef12": lambda: rmat(19, 12, permute=True, symmetric=True, seed=BASE_SEED + 55),
+    "w_rmat17_ef40": lambda: rmat(17, 40, permute=False, symmetric=False, seed=BASE_SEED + 56),
+    "w_road_mid": lambda: road_grid(1000, 600, mean_draw=2.5, seed=BASE_SEED + 57),
+    "w_cliques_40": lambda: cliques(150_000, 40.0, 0.15, BASE_SEED + 58),
+}
+EXTRA.update(EXTRA4)
+
 
 def cliques(n: int, mean_size: float, noise: float, seed: int) -> Graph:
     """Co-authorship-like graph: consecutive ids are cut into cliques of 4 + Poisson(mean_size-4)

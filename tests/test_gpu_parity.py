@@ -324,6 +324,42 @@ def test_long_row_accumulation_stays_in_tolerance():
             _check(C, ref, bound, f"long row S={S} {kern}")
 
 
+@pytest.mark.parametrize("V", [1, 2])
+@pytest.mark.parametrize("K", [4, 6, 64, 68, 200])
+def test_split_panels_with_many_items_are_reduced_by_a_workgroup(V, K):
+    """Rows cut into 63 to 2000 items: panels with more than 64 partial rows are added up
+    by a workgroup each (16 threads per vector of C, then their partial sums), the others by
+    one thread per vector.  Both must match the oracle, give the same bits on a second run
+    over different garbage, and the same bits from the host-built, the GPU-built and the
+    column-ordered handle."""
+    SG = 4
+    lengths = [63 * SG, 64 * SG, 64 * SG + 1, 65 * SG, 66 * SG, 200 * SG + 3, 2000 * SG, 1, 0, 7, 129 * SG]
+    if V == 2:
+        lengths.append(300 * SG)  # an odd number of rows: the last panel has one row
+    rng = np.random.default_rng(5 + K)
+    n_cols = 9001
+    rowptr = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    colidx = np.concatenate([np.sort(rng.choice(n_cols, L, replace=False)) for L in lengths]).astype(np.int32)
+    vals = rng.uniform(-1.0, 1.0, colidx.shape[0]).astype(np.float32)
+    g = synth.Graph("many_items", len(lengths), n_cols, rowptr, colidx, vals)
+    B = synth.dense_operand(n_cols, K, "normal", 23)
+    ref, bound = oracle.spmm(g.rowptr, g.colidx, g.vals, B)
+    Bd = torch.from_numpy(B).cuda()
+    outs = []
+    for flags in (0, pc.PCSR_FLAG_GPU_BUILD, pc.PCSR_FLAG_COLUMN_ORDER):
+        h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals,
+                          pc.make_params(V=V, S=1, SG=SG, flags=flags))
+        for fill in (float("nan"), -3e33):
+            Cd = torch.full((g.n_rows, K), fill, dtype=torch.float32, device="cuda")
+            pc.pcsr_spmm(h, Bd, Cd, K)
+            torch.cuda.synchronize()
+            outs.append(Cd.cpu().numpy())
+        h.close()
+    _check(outs[0], ref, bound, f"V={V} K={K}")
+    for o in outs[1:]:
+        assert np.array_equal(outs[0].view(np.uint32), o.view(np.uint32))
+
+
 _FULL = {}
 
 

@@ -301,7 +301,17 @@ def test_reorder_by_degree():
 
 def test_selector_proposes_the_window_only_where_the_build_keeps_it():
     g = synth.workload("sbm", "small")                       # 24 communities of 500 consecutive ids
-    sel = pc.pcsr_select(pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx), 128)
+    f = np.array(pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx), dtype=np.float64)
+    # 12,000 rows give 24 window blocks: far too few for 256 compute units, so no window
+    small = pc.pcsr_select(f, 128)
+    assert small.col_window == 0 and small.S == 0 and small.V == 1
+    f[0] = f[1] = 250_000                                    # the same structure at the full size
+    assert pc.pcsr_select(f, 32).col_window == 0            # narrow B rows: the plain kernel ties
+    assert pc.pcsr_select(f, 64).col_window == 512
+    f[0] = f[1] = 150_000
+    assert pc.pcsr_select(f, 64).col_window == 0            # 150,000 rows x 1 slice: too few blocks
+    f[0] = f[1] = 250_000
+    sel = pc.pcsr_select(f, 128)
     assert sel.col_window == 512 and sel.S == 0 and sel.flags & pc.PCSR_FLAG_WINDOW_IF_USEFUL
     sel.flags |= HOST
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, sel)
@@ -311,7 +321,18 @@ def test_selector_proposes_the_window_only_where_the_build_keeps_it():
     h.close()
     # the same request on the shuffled graph: the build finds no blocks and drops the window
     gs = synth.workload("sbm_shuffled", "small")
-    assert pc.pcsr_select(pc.pcsr_features(gs.n_rows, gs.n_cols, gs.rowptr, gs.colidx), 128).col_window == 0
+    fs = np.array(pc.pcsr_features(gs.n_rows, gs.n_cols, gs.rowptr, gs.colidx), dtype=np.float64)
+    shuffled = pc.pcsr_select(fs, 128)
+    # long rows, scattered columns: items of 32 in column order from K = 64, paired rows below
+    assert shuffled.col_window == 0 and shuffled.S == 1 and shuffled.SG == 32
+    assert shuffled.flags & pc.PCSR_FLAG_COLUMN_ORDER and shuffled.lanes_per_row == 16
+    narrow = pc.pcsr_select(fs, 32)                           # too few rows to pair them
+    assert narrow.S == 0 and narrow.V == 1 and narrow.col_window == 0
+    fs[0] = fs[1] = 250_000
+    fs[16] = 0.002                                            # near-diagonal share of uniform columns at that size
+    assert pc.pcsr_select(fs, 128).col_window == 0
+    narrow = pc.pcsr_select(fs, 32)
+    assert narrow.S == 0 and narrow.V == 2 and narrow.waves_per_wg == 2
     h = pc.pcsr_build(gs.n_rows, gs.n_cols, gs.rowptr, gs.colidx, gs.vals, sel)
     assert pc.pcsr_window_stats(h)["col_window"] == 0
     q = pc.pcsr_query_launch(h, 128)
