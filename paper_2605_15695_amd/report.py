@@ -12,7 +12,7 @@ import math
 import sys
 
 
-def records_table(recs) -> None:
+def records_table(recs, top: int = 6) -> None:
     """Compact view of the recorded sweep: per input, the best median time of every format tuple
     (over launch shapes) and of every launch shape (over formats), relative to the input's best."""
     keys = sorted({(r["workload"], r["K"]) for r in recs if r.get("kind") == "pcsr"})
@@ -30,7 +30,7 @@ def records_table(recs) -> None:
                 k = name(r)
                 if k not in by or r["ms_median"] < by[k]["ms_median"]:
                     by[k] = r
-            rows = sorted(by.items(), key=lambda kv: kv[1]["ms_median"])[:6]
+            rows = sorted(by.items(), key=lambda kv: kv[1]["ms_median"])[:top]
             print(f"| {title} | best ms | % of input's best | reached with |")
             print("|---|---|---|---|")
             for k, r in rows:
@@ -44,12 +44,17 @@ def main(argv=None) -> int:
     records = "--records" in paths
     if records:
         paths.remove("--records")
+    top = 6
+    for p in list(paths):
+        if p.startswith("--top="):
+            top = int(p.split("=", 1)[1])
+            paths.remove(p)
     recs = []
     for p in paths:
         with open(p) as f:
             recs += [json.loads(line) for line in f if line.strip()]
     if records:
-        records_table(recs)
+        records_table(recs, top)
         return 0
     keys = sorted({(r["workload"], r["K"]) for r in recs if r.get("kind") == "pcsr"})
     print("| workload | K | n | nnz | best tuple (V,S,SG[c = column-ordered] / lanes,vec,rep,waves,items) | ms | GFLOP/s | roofline frac "
