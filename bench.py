@@ -27,17 +27,17 @@ HBM_PEAK_GBS = 8000.0
 # that was profiled, the item size SG and the item schedule: a run that launches another
 # instance, or the same instance over another PCSR layout, reports null.
 PROFILED_TRAFFIC = {
-    ("poisson-full", 32, "spmm_kernel<1, false, 8, 4, 1>", 0, "index"): 3509284,
-    ("road-full", 128, "spmm_kernel<2, false, 32, 4, 1>", 0, "index"): 2121477869,
-    ("rmat20-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 2050053979,
-    ("sbm-full", 256, "spmm_window_kernel<1, 16, 4, 1>", 0, "index"): 2229595538,
-    ("sbm_shuffled-full", 256, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 10018841746,
-    ("rmat22-full", 16, "spmm_kernel<1, true, 4, 4, 1>", 32, "column"): 10717798985,
-    ("rmat22-full", 32, "spmm_kernel<1, true, 8, 4, 1>", 32, "column"): 9828954459,
-    ("rmat22-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 17903178313,
-    ("rmat22-full", 128, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 36025956699,
-    ("rmat22-full", 256, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 75013965915,
-    ("rmat22-full", 512, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 155938165668,
+    ("poisson-full", 32, "spmm_kernel<1, false, 8, 4, 1>", 0, "index"): 3503085,
+    ("road-full", 128, "spmm_kernel<2, false, 32, 4, 1>", 0, "index"): 2121481179,
+    ("rmat20-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 2050060690,
+    ("sbm-full", 256, "spmm_window_kernel<1, 16, 4, 1>", 0, "index"): 2230701604,
+    ("sbm_shuffled-full", 256, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 10018994230,
+    ("rmat22-full", 16, "spmm_kernel<1, true, 4, 4, 1>", 32, "column"): 10724983945,
+    ("rmat22-full", 32, "spmm_kernel<1, true, 8, 4, 1>", 32, "column"): 9844466834,
+    ("rmat22-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 17907130971,
+    ("rmat22-full", 128, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 36026222500,
+    ("rmat22-full", 256, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 75014491538,
+    ("rmat22-full", 512, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 155942151679,
 }
 
 

@@ -21,10 +21,9 @@
 #include <set>
 #include <utility>
 
-// registers of B data a lane keeps in flight per gather step (32 measured within 2 % of 16
-// on the unsplit inputs and 20 % slower on one of them)
+// registers of B data a lane keeps in flight per gather step
 #define PCSR_INFLIGHT 16
-// balanced (power-law) inputs gather scattered lines: twice as deep
+// balanced (power-law) inputs gather scattered lines: twice as deep (see spmm_kernel)
 #define PCSR_INFLIGHT_SPLIT 32
 // gathers per step at most
 #define PCSR_MAXSTEP 8
@@ -190,8 +189,12 @@ template <int V, bool S, int LPR, int VEC, int REP>
 __global__ void __launch_bounds__(512) spmm_kernel(SpmmArgs a)
 {
     constexpr int G = 64 / LPR;
-    // vectors gathered per inner step: about 16 registers of B data in flight
-    constexpr int U0 = (S ? PCSR_INFLIGHT_SPLIT : PCSR_INFLIGHT) / (REP * VEC);
+    // vectors gathered per inner step: 16 registers of B data in flight, 32 for balanced
+    // handles and for V = 1 with groups of up to 8 lanes (K <= 32: 4-8 % faster on rows of 40
+    // and more nonzeros, no different on short rows; with V = 2 it costs road-like inputs
+    // 2-7 %, and with wider groups it changes nothing)
+    constexpr bool DEEP = S || (V == 1 && LPR <= 8);
+    constexpr int U0 = (DEEP ? PCSR_INFLIGHT_SPLIT : PCSR_INFLIGHT) / (REP * VEC);
     constexpr int Uc = U0 < 1 ? 1 : (U0 > PCSR_MAXSTEP ? PCSR_MAXSTEP : U0);
     constexpr int U = Uc > LPR ? LPR : Uc; // a step never reaches past the group's chunk
     const int lane = threadIdx.x & 63;
