@@ -206,11 +206,11 @@ def main() -> int:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            torch.mul(src, 1.0, out=dst)
         cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
         for a, b in cev:
             a.record(stream)
-            dst.copy_(src)
+            torch.mul(src, 1.0, out=dst)   # an elementwise kernel; copy_() may go through the DMA engines
             b.record(stream)
         torch.cuda.synchronize()
         stream_gbs = 2.0 * src.numel() * 4 / (statistics.median(a.elapsed_time(b) for a, b in cev) * 1e-3) / 1e9

@@ -42,8 +42,63 @@ __global__ void validate_kernel(int64_t n_rows, int64_t n_cols, int64_t nnz, con
     }
 }
 
-// V = 2: distinct columns in the union of rows 2p and 2p+1
-__global__ void count_union_kernel(int64_t P, int64_t n_rows, const int32_t *rowptr, const int32_t *colidx,
+// V = 2, one thread per nonzero, so that a row of 100,000 nonzeros is merged by 100,000
+// threads and not by one.  The vectors of panel p are the sorted union of the columns of
+// rows 2p ("even") and 2p+1 ("odd"); an element's place in the union follows from two
+// counts: the elements of its own row before it, and those of the other row that are
+// smaller and not already counted (columns present in both rows are counted with the even
+// row).
+
+// index of the row that holds nonzero t: the last r with rowptr[r] <= t
+__device__ __forceinline__ int64_t row_of_nonzero(const int32_t *rowptr, int64_t n_rows, int64_t t)
+{
+    int64_t lo = 0, hi = n_rows; // rowptr[lo] <= t < rowptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= t)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return lo;
+}
+
+// number of entries of colidx[b, e) smaller than c
+__device__ __forceinline__ int64_t count_below(const int32_t *colidx, int64_t b, int64_t e, int32_t c)
+{
+    int64_t lo = b, hi = e;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (colidx[mid] < c)
+            lo = mid + 1;
+        else
+            hi = mid;
+    }
+    return lo - b;
+}
+
+// shared[t] = 1 for a nonzero of an odd row whose column also occurs in the even row of
+// its panel, else 0; shared[nnz] = 0 (scanned together with the rest)
+__global__ void union_shared_kernel(int64_t n_rows, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                                    int32_t *shared)
+{
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t > nnz) return;
+    int32_t flag = 0;
+    if (t < nnz) {
+        const int64_t r = row_of_nonzero(rowptr, n_rows, t);
+        if (r & 1) {
+            const int64_t a0 = rowptr[r - 1], a1 = rowptr[r];
+            const int32_t c = colidx[t];
+            const int64_t k = count_below(colidx, a0, a1, c);
+            flag = (a0 + k < a1 && colidx[a0 + k] == c) ? 1 : 0;
+        }
+    }
+    shared[t] = flag;
+}
+
+// vectors per panel: both rows' nonzeros minus the columns they share; cnt[P] = 0
+__global__ void union_count_kernel(int64_t P, int64_t n_rows, const int32_t *rowptr, const int32_t *shared_scan,
                                    int32_t *cnt)
 {
     const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -53,37 +108,40 @@ __global__ void count_union_kernel(int64_t P, int64_t n_rows, const int32_t *row
         return;
     }
     const int64_t r0 = 2 * p;
-    int64_t a = rowptr[r0], ae = rowptr[r0 + 1];
-    int64_t b = ae, be = (r0 + 1 < n_rows) ? rowptr[r0 + 2] : ae, n = 0;
-    while (a < ae && b < be) {
-        const int32_t ca = colidx[a], cb = colidx[b];
-        a += (ca <= cb);
-        b += (cb <= ca);
-        ++n;
-    }
-    cnt[p] = (int32_t)(n + (ae - a) + (be - b));
+    const int64_t a0 = rowptr[r0], a1 = rowptr[r0 + 1];
+    const int64_t b1 = (r0 + 1 < n_rows) ? rowptr[r0 + 2] : a1;
+    cnt[p] = (int32_t)((b1 - a0) - (shared_scan[b1] - shared_scan[a1]));
 }
 
-// V = 2: merge the two rows of a panel into vectors (ascending column, +0.0f padding)
-__global__ void fill_union_kernel(int64_t P, int64_t n_rows, const int32_t *rowptr, const int32_t *colidx,
-                                  const float *vals, const int32_t *prow, int32_t *out_col, float *out_val)
+// every nonzero writes its vector (ascending column, +0.0f padding); a column that both
+// rows hold is written by the even row's nonzero
+__global__ void union_fill_kernel(int64_t n_rows, int64_t nnz, const int32_t *rowptr, const int32_t *colidx,
+                                  const float *vals, const int32_t *shared_scan, const int32_t *prow,
+                                  int32_t *out_col, float *out_val)
 {
-    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p >= P) return;
-    const int64_t r0 = 2 * p;
-    int64_t a = rowptr[r0], ae = rowptr[r0 + 1];
-    int64_t b = ae, be = (r0 + 1 < n_rows) ? rowptr[r0 + 2] : ae;
-    int64_t o = prow[p];
-    while (a < ae || b < be) {
-        const int32_t ca = a < ae ? colidx[a] : INT32_MAX;
-        const int32_t cb = b < be ? colidx[b] : INT32_MAX;
-        const int32_t c = ca < cb ? ca : cb;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= nnz) return;
+    const int64_t r = row_of_nonzero(rowptr, n_rows, t);
+    const int64_t p = r >> 1;
+    const int32_t c = colidx[t];
+    const int64_t a0 = rowptr[2 * p], a1 = rowptr[2 * p + 1];
+    const int64_t b1 = (2 * p + 1 < n_rows) ? rowptr[2 * p + 2] : a1;
+    if (!(r & 1)) {
+        const int64_t k = count_below(colidx, a1, b1, c);                // odd-row columns below c
+        const int64_t both = shared_scan[a1 + k] - shared_scan[a1];       // of which also in this row
+        const int64_t o = prow[p] + (t - a0) + (k - both);
+        const bool twin = a1 + k < b1 && colidx[a1 + k] == c;
+        if (o >= prow[p + 1]) return; // only with rows that are not sorted (validation skipped)
         out_col[o] = c;
-        out_val[2 * o] = (ca == c) ? vals[a] : 0.0f;
-        out_val[2 * o + 1] = (cb == c) ? vals[b] : 0.0f;
-        a += (ca == c);
-        b += (cb == c);
-        ++o;
+        out_val[2 * o] = vals[t];
+        out_val[2 * o + 1] = twin ? vals[a1 + k] : 0.0f;
+    } else if (shared_scan[t + 1] == shared_scan[t]) {                    // not shared
+        const int64_t k = count_below(colidx, a0, a1, c);                // even-row columns below c
+        const int64_t o = prow[p] + k + ((t - a1) - (shared_scan[t] - shared_scan[a1]));
+        if (o >= prow[p + 1]) return;
+        out_col[o] = c;
+        out_val[2 * o] = 0.0f;
+        out_val[2 * o + 1] = vals[t];
     }
 }
 
@@ -567,10 +625,17 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
             HIP_TRY(hipMemcpy(pval, d_vals, sizeof(float) * nnz, hipMemcpyDeviceToDevice));
         }
     } else {
-        int32_t *cnt = nullptr;
+        if (nnz + 1 > 0x7fffffffLL) return PCSR_E_TOO_LARGE; // the scan below counts in int32
+        int32_t *cnt = nullptr, *shared = nullptr, *shared_scan = nullptr;
         HIP_TRY(sc.alloc((void **)&cnt, sizeof(int32_t) * (P + 1)));
-        hipLaunchKernelGGL(count_union_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, n_rows,
-                           d_rowptr, d_colidx, cnt);
+        HIP_TRY(sc.alloc((void **)&shared, sizeof(int32_t) * (nnz + 1)));
+        HIP_TRY(sc.alloc((void **)&shared_scan, sizeof(int32_t) * (nnz + 1)));
+        hipLaunchKernelGGL(union_shared_kernel, dim3(blocks_for(nnz + 1)), dim3(kThreads), 0, 0, n_rows, nnz,
+                           d_rowptr, d_colidx, shared);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(exclusive_scan(shared, shared_scan, nnz + 1, sc));
+        hipLaunchKernelGGL(union_count_kernel, dim3(blocks_for(P + 1)), dim3(kThreads), 0, 0, P, n_rows,
+                           d_rowptr, shared_scan, cnt);
         HIP_TRY(hipGetLastError());
         HIP_TRY(exclusive_scan(cnt, prow, P + 1, sc));
         int32_t total = 0;
@@ -578,9 +643,9 @@ int build_device(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *d_r
         nnz_v = total;
         HIP_TRY(sc.alloc((void **)&pcol, sizeof(int32_t) * (nnz_v + 1)));
         HIP_TRY(sc.alloc((void **)&pval, sizeof(float) * (2 * nnz_v + 1)));
-        if (P > 0) {
-            hipLaunchKernelGGL(fill_union_kernel, dim3(blocks_for(P)), dim3(kThreads), 0, 0, P, n_rows,
-                               d_rowptr, d_colidx, d_vals, prow, pcol, pval);
+        if (nnz > 0) {
+            hipLaunchKernelGGL(union_fill_kernel, dim3(blocks_for(nnz)), dim3(kThreads), 0, 0, n_rows, nnz,
+                               d_rowptr, d_colidx, d_vals, shared_scan, prow, pcol, pval);
             HIP_TRY(hipGetLastError());
         }
     }

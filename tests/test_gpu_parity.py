@@ -378,8 +378,9 @@ def _sample_rows(g, n_random=20000):
                                      np.argsort(deg)[-50:], np.nonzero(deg == 0)[0][:50]]))
 
 
-@pytest.mark.parametrize("name,K", [("road", 128), ("rmat20", 64), ("sbm", 256), ("sbm_shuffled", 256),
-                                    ("rmat22", 32)])
+@pytest.mark.parametrize("name,K", [("poisson", 32), ("road", 128), ("rmat20", 64), ("sbm", 256),
+                                    ("sbm_shuffled", 256), ("rmat22", 16), ("rmat22", 32), ("rmat22", 64),
+                                    ("rmat22", 128)])
 def test_full_size_sampled_rows(name, K):
     """Every benchmark workload at full size in the launch configuration bench.py times
     (the library's own pick); the oracle recomputes a sample of rows one by one, the
