@@ -32,7 +32,7 @@ PROFILED_TRAFFIC = {
     ("rmat20-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 2050060690,
     ("sbm-full", 256, "spmm_window_kernel<1, 16, 4, 1>", 0, "index"): 2230701604,
     ("sbm_shuffled-full", 256, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 10018994230,
-    ("rmat22-full", 16, "spmm_kernel<1, true, 4, 4, 1>", 32, "column"): 10724983945,
+    ("rmat22-full", 16, "spmm_kernel<1, true, 16, 1, 1>", 32, "column"): 6858113234,
     ("rmat22-full", 32, "spmm_kernel<1, true, 8, 4, 1>", 32, "column"): 9844466834,
     ("rmat22-full", 64, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 17907130971,
     ("rmat22-full", 128, "spmm_kernel<1, true, 16, 4, 1>", 32, "column"): 36026222500,

@@ -724,7 +724,14 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // rows at about the same time (R-MAT scale 22: 1.6-2x over the best index-order tuple at
     // every width from 16 to 512; neutral on small or uniform inputs).
     const bool skewed = cv > 1.5 && d_max > 256.0;
-    const int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
+    // Loads per lane: the widest vector that divides K, except where fewer rows per
+    // wavefront pay more than wide loads.  A wavefront runs until the longest of its work
+    // items ends, so with rows of varying length every further item per wavefront costs
+    // lane time.  K of 9..16: one dword per lane, 16 lanes per row (4 items per wavefront
+    // instead of 16: 11-18 % faster on every input but road-like ones, whose rows of 3 want
+    // many rows per wavefront).
+    int vec = K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1);
+    if (K > 8 && K <= 16 && d_hat >= 8.0) vec = 1;
     // Rows that gather from a neighbourhood of their own index are served from LDS instead
     // (see the column window below), from K = 64 (at 32 it ties with the plain kernel) and if
     // the product is large enough to give every compute unit a few window blocks: a block
@@ -746,7 +753,14 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
     // lane group has in flight.  Rows with local columns lose up to half their speed under
     // the column order (it gives up the reuse between neighbouring rows).
     const bool scattered = f[16] < 4.0 * 1025.0 / (n > 1.0 ? n : 1.0);
-    const bool long_uniform = !skewed && !windowed && d_hat >= 40.0 && scattered;
+    // K of 17..32 with scattered columns and a B beyond 16 MB (rows gathered from the
+    // memory side, not from L2): one dword per lane again, a row per half wavefront
+    // (uniform random columns, 16 to 64 per row, 150,000 rows or more: 7-24 % faster than
+    // the best 16-byte shape; slower when B is small or the columns are local).
+    const bool wide_scatter = !skewed && scattered && d_hat >= 12.0 && K > 16 && K <= 32 &&
+                              n * (double)K * 4.0 > 16.0 * 1048576.0;
+    if (wide_scatter) vec = 1;
+    const bool long_uniform = !skewed && !windowed && !wide_scatter && d_hat >= 40.0 && scattered;
     const bool long_uniform_wide = long_uniform && K >= 64;
     p.S = (skewed || long_uniform_wide) ? 1 : 0;
     p.SG = p.S ? 32 : 0; // power-law inputs: raised to 64 below for 128-column slices

@@ -43,7 +43,9 @@ def kernel_shapes(K: int, quick: bool):
     for vec in (4, 2, 1):
         if K % vec:
             continue
-        if quick and vec != (4 if K % 4 == 0 else (2 if K % 2 == 0 else 1)):
+        # quick: only the widest vector load, except for K <= 32, where narrower loads
+        # (fewer rows per wavefront) win on some inputs
+        if quick and K > 32 and vec != (4 if K % 4 == 0 else (2 if K % 2 == 0 else 1)):
             continue
         for lpr in (4, 8, 16, 32, 64):
             for rep in (1, 2, 4):
@@ -92,7 +94,7 @@ def main(argv=None) -> int:
     ap.add_argument("--size", default="full")
     ap.add_argument("--K", type=int, nargs="*", default=None)
     ap.add_argument("--out", required=True)
-    ap.add_argument("--quick", action="store_true", help="widest vector only, waves in {2,4}")
+    ap.add_argument("--quick", action="store_true", help="widest vector only (all widths for K <= 32), waves in {2,4}")
     ap.add_argument("--reps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--formats", default="all",

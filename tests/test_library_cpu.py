@@ -331,8 +331,18 @@ def test_selector_proposes_the_window_only_where_the_build_keeps_it():
     fs[0] = fs[1] = 250_000
     fs[16] = 0.002                                            # near-diagonal share of uniform columns at that size
     assert pc.pcsr_select(fs, 128).col_window == 0
+    narrow = pc.pcsr_select(fs, 32)                           # B = 32 MB, scattered: a dword per lane
+    assert (narrow.S, narrow.V, narrow.lanes_per_row, narrow.vec, narrow.rep) == (0, 1, 32, 1, 1)
+    fs[0] = fs[1] = 100_000                                   # B = 12.8 MB: rows paired instead
+    fs[16] = 0.005
     narrow = pc.pcsr_select(fs, 32)
-    assert narrow.S == 0 and narrow.V == 2 and narrow.waves_per_wg == 2
+    assert narrow.S == 0 and narrow.V == 2 and narrow.waves_per_wg == 2 and narrow.vec == 4
+    k16 = pc.pcsr_select(fs, 16)                              # K = 16: 16 lanes of one dword
+    assert (k16.lanes_per_row, k16.vec, k16.rep) == (16, 1, 1)
+    road = synth.workload("road", "small")
+    fr = pc.pcsr_features(road.n_rows, road.n_cols, road.rowptr, road.colidx)
+    r16 = pc.pcsr_select(fr, 16)                              # rows of 3: many rows per wavefront
+    assert (r16.V, r16.lanes_per_row, r16.vec) == (2, 4, 4)
     h = pc.pcsr_build(gs.n_rows, gs.n_cols, gs.rowptr, gs.colidx, gs.vals, sel)
     assert pc.pcsr_window_stats(h)["col_window"] == 0
     q = pc.pcsr_query_launch(h, 128)
