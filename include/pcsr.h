@@ -80,7 +80,9 @@ enum {
  *            (col_window + 1)*(lanes_per_row*vec*rep + 4)*4 bytes of LDS <= 160 KiB at launch.
  *   Kernel parameters (launch shape only; the paper's F and W):
  *     lanes_per_row  lanes cooperating on one work item: 4, 8, 16, 32 or 64; 0 = auto.
- *     vec            fp32 values per lane per B load: 1, 2 or 4; must divide K; 0 = auto.
+ *     vec            fp32 values per lane per B load: 1, 2 or 4; must divide K; 0 = auto
+ *                    (the widest that divides K; 1 for K of 9..16 when lanes_per_row is
+ *                    auto too and rows average 8 vectors or more).
  *     rep            column tiles per lane (the coarsening factor F): 1, 2 or 4; 0 = auto.
  *                    One work item covers lanes_per_row*vec*rep columns of C per grid.y
  *                    slice; wider K is covered by more grid.y slices.

@@ -130,6 +130,10 @@ int resolve_launch(pcsr_handle_t h, int32_t K, pcsr::LaunchShape *ls)
 {
     if (K <= 0) return PCSR_E_UNSUPPORTED;
     int vec = h->vec ? h->vec : (K % 4 == 0 ? 4 : (K % 2 == 0 ? 2 : 1));
+    // as pcsr_select: K of 9..16 is served by 16 lanes of one dword unless rows are very short
+    if (!h->vec && !h->lpr && K > 8 && K <= 16 && h->host.win_cols == 0 &&
+        h->host.nnz_v >= 8 * std::max<int64_t>(h->host.P, 1))
+        vec = 1;
     if (K % vec != 0) return PCSR_E_UNSUPPORTED;
     int lpr = h->lpr;
     if (!lpr) {

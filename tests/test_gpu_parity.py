@@ -650,7 +650,8 @@ def test_gpu_side_generation_degenerate_and_bad_input():
 def test_spmm_argument_checks():
     g = _graph("poisson")
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params())
-    K = 16
+    K = 32
+    assert pc.pcsr_query_launch(h, K)["vec"] == 4
     buf = torch.zeros((g.n_rows + g.n_cols) * K + 8, dtype=torch.float32, device="cuda")
     lib = pc.binding._lib()
     base = buf.data_ptr()

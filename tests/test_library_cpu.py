@@ -144,9 +144,11 @@ def test_error_paths():
 def test_launch_resolution():
     g = synth.workload("poisson", "small")
     h = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(flags=HOST))
-    q = pc.pcsr_query_launch(h, 16)
+    q = pc.pcsr_query_launch(h, 8)
     assert (q["lanes_per_row"], q["vec"], q["rep"]) == (4, 4, 1) and q["grid_y"] == 1
-    per_wg = q["waves_per_wg"] * 16
+    q = pc.pcsr_query_launch(h, 16)                      # rows of 8 on average: 16 lanes of one dword
+    assert (q["lanes_per_row"], q["vec"], q["rep"]) == (16, 1, 1) and q["grid_y"] == 1
+    per_wg = q["waves_per_wg"] * 4
     # one work-balanced item range per XCD: 8 x the workgroups of the longest range
     assert q["grid_x"] % 8 == 0 and -(-g.n_rows // per_wg) <= q["grid_x"] <= -(-g.n_rows // per_wg) + 64
     pc.pcsr_set_kernel_params(h, flags=pc.PCSR_FLAG_NO_XCD_REMAP)
