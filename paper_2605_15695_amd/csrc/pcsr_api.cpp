@@ -797,6 +797,14 @@ int pcsr_select(const double *f, int32_t K, pcsr_params_t *out)
         lpr >>= 1; // short rows: more rows per wavefront, two loads per lane
         rep = 2;
     }
+    // Scattered columns, rows of 8 to 40, K from 64: a 64-column slice per half wavefront
+    // with dwordx2 loads (uniform random columns, 8 to 32 per row, K = 64 and 128: 3-7 %
+    // over the best 16-byte shape; local columns keep the 16-byte shapes).
+    if (!skewed && !windowed && !long_uniform && scattered && d_hat >= 8.0 && K >= 64 && K % 2 == 0) {
+        lpr = 32;
+        vec = 2;
+        rep = 1;
+    }
     p.lanes_per_row = lpr;
     p.vec = vec;
     p.rep = rep;

@@ -45,7 +45,13 @@ def kernel_shapes(K: int, quick: bool):
             continue
         # quick: only the widest vector load, except for K <= 32, where narrower loads
         # (fewer rows per wavefront) win on some inputs
-        if quick and K > 32 and vec != (4 if K % 4 == 0 else (2 if K % 2 == 0 else 1)):
+        widest = 4 if K % 4 == 0 else (2 if K % 2 == 0 else 1)
+        if quick and K > 32 and vec != widest:
+            # ... and the two 64-column slices built from narrow loads
+            if 64 * 8 >= K and K % 2 == 0 and vec == 2:
+                shapes.append((32, 2, 1))
+            elif 64 * 8 >= K and vec == 1:
+                shapes.append((64, 1, 1))
             continue
         for lpr in (4, 8, 16, 32, 64):
             for rep in (1, 2, 4):

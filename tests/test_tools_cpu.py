@@ -16,7 +16,10 @@ def test_kernel_shapes_cover_k_without_idle_repeats():
             assert tile * 8 >= K                       # at most 8 grid.y slices
             assert lpr * vec * (rep - 1) < K           # no repeat entirely past K
     quick = sweep.kernel_shapes(128, quick=True)
-    assert quick and all(v == 4 for _, v, _ in quick)
+    # the widest load, plus the two 64-column slices made of narrow loads
+    assert quick and all(v == 4 or (l, v, r) in ((32, 2, 1), (64, 1, 1)) for l, v, r in quick)
+    assert (32, 2, 1) in quick and (64, 1, 1) in quick
+    assert {v for _, v, _ in sweep.kernel_shapes(32, quick=True)} == {1, 2, 4}
 
 
 def test_report_table_and_geomean(tmp_path):
