@@ -186,6 +186,50 @@ def test_select_returns_valid_tuple():
         synth.workload("road", "small"))), 64).S == 0
 
 
+def test_select_always_returns_a_tuple_the_library_can_launch():
+    """Whatever the features (random, extreme, non-finite) and the width, the rule returns
+    parameters inside the documented domains, and a handle built from them resolves to a
+    launch shape that exists."""
+    rng = np.random.default_rng(11)
+    g = synth.workload("sbm", "small")
+    base = np.array(pc.pcsr_features(g.n_rows, g.n_cols, g.rowptr, g.colidx), dtype=np.float64)
+    handles = {}
+    for trial in range(400):
+        f = base.copy()
+        if trial % 4:
+            f[0] = f[1] = float(rng.choice([1, 50, 4096, 90_000, 250_000, 4_000_000, 2**31 - 1]))
+            f[4] = f[5] = float(rng.choice([0.0, 1.0, 3.0, 7.9, 12.0, 39.9, 40.0, 200.0, 1e5]))
+            f[6] = f[5] * float(rng.choice([1.0, 2.0, 100.0, 1e4]))
+            f[7] = f[8] = float(rng.choice([0.0, 0.1, 1.49, 1.51, 8.0]))
+            f[15] = float(rng.choice([0.0, 0.1, 0.19, 0.2, 0.3, 0.45, 0.5]))
+            f[16] = float(rng.choice([0.0, 1e-4, 0.01, 0.3, 0.6, 0.9, 1.0]))
+        if trial % 50 == 49:
+            f[int(rng.integers(0, f.shape[0]))] = float(rng.choice([np.nan, np.inf, -np.inf, -1.0]))
+        K = int(rng.choice([1, 2, 3, 7, 8, 9, 12, 16, 17, 24, 32, 33, 48, 64, 96, 100, 128, 255, 256, 512, 2048]))
+        p = pc.pcsr_select(f, K)
+        assert p.V in (1, 2) and p.S in (0, 1) and p.SG >= 0 and p.omega in (0, 32, 64)
+        assert p.lanes_per_row in (4, 8, 16, 32, 64) and p.vec in (1, 2, 4) and K % p.vec == 0
+        assert p.rep in (1, 2, 4) and 1 <= p.waves_per_wg <= 16 and p.items_per_group in (0, 1)
+        assert p.col_window in (0, 512)
+        if p.col_window:
+            assert (p.col_window + 1) * (p.lanes_per_row * p.vec * p.rep + 4) * 4 <= 160 * 1024
+            assert p.S == 0 and p.V == 1 and p.flags & pc.PCSR_FLAG_WINDOW_IF_USEFUL
+        if p.flags & pc.PCSR_FLAG_COLUMN_ORDER:
+            assert p.S == 1
+        # the launch shape exists for a handle of that format (built once per format)
+        key = (p.V, p.S, min(p.SG, 64), p.col_window, p.flags & pc.PCSR_FLAG_COLUMN_ORDER)
+        if key not in handles:
+            handles[key] = pc.pcsr_build(g.n_rows, g.n_cols, g.rowptr, g.colidx, g.vals, pc.make_params(
+                V=p.V, S=p.S, SG=key[2], col_window=p.col_window, flags=HOST | key[4]))
+        h = handles[key]
+        pc.pcsr_set_kernel_params(h, p.lanes_per_row, p.vec, p.rep, p.waves_per_wg, 0)
+        q = pc.pcsr_query_launch(h, K)
+        assert q["lanes_per_row"] == p.lanes_per_row and q["vec"] == p.vec and q["grid_y"] >= 1
+        assert q["lanes_per_row"] * q["vec"] * q["rep"] * q["grid_y"] >= K
+    for h in handles.values():
+        h.close()
+
+
 def test_reorder_is_a_permutation_and_recovers_planted_clusters():
     g = synth.workload("sbm_shuffled", "small")          # 24 blocks of 500, ids shuffled
     perm, ncl = pc.pcsr_reorder(g.n_rows, g.rowptr, g.colidx)
